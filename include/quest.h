@@ -1,0 +1,144 @@
+/*
+ * quest.h -- C ABI of the Quest decode hot path for AMD MI355X (gfx950).
+ *
+ * Quest (arXiv 2406.10774) keeps the whole KV cache, organised in pages, and
+ * at every decode step (i) scores each page with an upper bound of the
+ * attention logit any of its tokens can reach, computed from the channel-wise
+ * min and max of the page's keys, (ii) keeps the K best pages and (iii) runs
+ * ordinary decode attention over those pages only (Section 3.4, Algorithm 1
+ * and Figure 5 of the paper).  This library is that path, one call per step:
+ *
+ *     after prefill :  quest_build_meta
+ *     every token   :  quest_append_meta -> quest_estimate -> quest_topk
+ *                      -> quest_sparse_decode
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller.  The library
+ *     never allocates or frees device memory and keeps no state between calls.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work on that stream; they never synchronise.
+ *   - The return value is a quest_status; 0 means "enqueued".  Only facts the
+ *     host can see are validated (null pointers, unsupported head_dim /
+ *     page_size, k_pages < 1, workspace too small, a failed launch).  What
+ *     lives in device memory (seq_lens, page_table, topk_idx) is trusted:
+ *     1 <= seq_lens[b] <= max_pages_per_seq * page_size, and every logical
+ *     page that holds a token maps to a physical page < num_phys_pages.
+ *   - fp16 means IEEE binary16.  Keys, values and queries must be finite
+ *     (NaN/Inf in a *valid* slot is undefined behaviour; stale slots beyond
+ *     seq_lens are never used, whatever they contain).
+ *   - Supported shapes: head_dim == 128, page_size == 16, multi-head attention
+ *     (one KV head per query head).
+ *
+ * Layouts (row-major, innermost last)
+ *   k_pool, v_pool : fp16  [num_phys_pages][num_heads][page_size][head_dim]
+ *   meta           : fp16  [num_phys_pages][num_heads][2][head_dim]
+ *                          [..][0][:] = channel-wise min, [..][1][:] = max
+ *   page_table     : int32 [batch][max_pages_per_seq]; logical page p of
+ *                          sequence b (tokens [p*S, p*S+S)) -> physical page
+ *   seq_lens       : int32 [batch], tokens currently valid
+ *   q, k_new, v_new: fp16  [batch][num_heads][head_dim]
+ *   scores         : fp32  [batch][num_heads][max_pages_per_seq]
+ *   topk_idx       : int32 [batch][num_heads][k_pages]
+ *   out            : fp32 or fp16 [batch][num_heads][head_dim]
+ *   lse            : fp32  [batch][num_heads]
+ */
+#ifndef QUEST_H_
+#define QUEST_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum quest_status {
+  QUEST_OK = 0,
+  QUEST_ERR_NULL = -1,        /* a required pointer is NULL                  */
+  QUEST_ERR_SHAPE = -2,       /* a size is < 1 or exceeds a launch limit     */
+  QUEST_ERR_UNSUPPORTED = -3, /* head_dim != 128 or page_size != 16          */
+  QUEST_ERR_WORKSPACE = -4,   /* workspace NULL or smaller than required     */
+  QUEST_ERR_HIP = -5          /* the HIP runtime refused the launch          */
+} quest_status;
+
+/* Description of one layer's paged KV cache.  Host struct, passed by pointer;
+ * the library reads it during the call only. */
+typedef struct quest_cache {
+  int32_t batch;              /* B >= 1                                      */
+  int32_t num_heads;          /* H >= 1                                      */
+  int32_t head_dim;           /* D, must be 128                              */
+  int32_t page_size;          /* S, must be 16                               */
+  int32_t max_pages_per_seq;  /* row stride of page_table and of scores      */
+  int32_t reserved;           /* set to 0                                    */
+  int64_t num_phys_pages;     /* capacity of the pools, in pages             */
+  void* k_pool;               /* device, fp16                                */
+  void* v_pool;               /* device, fp16                                */
+  void* meta;                 /* device, fp16                                */
+  const int32_t* page_table;  /* device                                      */
+  const int32_t* seq_lens;    /* device                                      */
+} quest_cache;
+
+/* Bytes of device workspace quest_sparse_decode needs for this cache and
+ * k_pages (k_pages <= 0: the dense path over all pages).  Pure host function.
+ * The workspace holds the split-K partial results (running max, denominator
+ * and un-normalised accumulator of each split).  *out_bytes may be 0. */
+int quest_workspace_bytes(const quest_cache* cache, int32_t k_pages, size_t* out_bytes);
+
+/* Metadata of every page that holds at least one token (Section 3.4:
+ * "maximum and minimum values of each feature dimension of the Key vector"):
+ *   meta[phys][h][0][i] = min_j k[j][i],  meta[phys][h][1][i] = max_j k[j][i]
+ * over the valid tokens j of the page (a partial last page: its first
+ * seq_len - p*S slots).  Comparison is by value with -0 ordered below +0, so
+ * the result is independent of reduction order and bit-exact.  Entries of
+ * pages without tokens are not written.  To be called once after prefill;
+ * also the recovery path (metadata is a pure function of the keys). */
+int quest_build_meta(const quest_cache* cache, void* stream);
+
+/* Insertion half of Algorithm 1.  seq_lens[b] already counts the new token,
+ * which sits at position L-1: slot (L-1) % S of logical page (L-1) / S.
+ * If k_pool_write != 0 the token's key and value (v_new must then be
+ * non-NULL) are first stored into that slot of k_pool / v_pool.  Then the key
+ * is folded into the page's entry: slot 0 opens the page (min = max = k),
+ * otherwise max = max(max, k), min = min(min, k) per channel, same ordering
+ * as quest_build_meta.  v_new may be NULL when k_pool_write == 0. */
+int quest_append_meta(const quest_cache* cache, const void* k_new, const void* v_new,
+                      int32_t k_pool_write, void* stream);
+
+/* Attention half of Algorithm 1: for every sequence b, head h and logical
+ * page p < ceil(seq_lens[b] / S),
+ *   scores[b][h][p] = sum_i max(q[i] * min[p][i], q[i] * max[p][i]),
+ * unscaled; fp16 products are exact in fp32, accumulation is fp32.  Entries
+ * p >= ceil(seq_lens[b]/S) of a row are not written. */
+int quest_estimate(const quest_cache* cache, const void* q, float* scores, void* stream);
+
+/* Top-K filtering (Section 3.4): for every (b, h) the K_b = min(k_pages, P_b)
+ * pages with the largest score among the P_b = ceil(seq_lens[b]/S) valid ones.
+ * Scores compare by value (-0 == +0); of equal scores the lower page index is
+ * kept.  topk_idx[b][h][0..K_b) receives the chosen logical page ids in
+ * ascending order, the rest of the row is set to -1.  k_eff (nullable, int32
+ * [batch], device) receives K_b.  Deterministic. */
+int quest_topk(const quest_cache* cache, const float* scores, int32_t k_pages,
+               int32_t* topk_idx, int32_t* k_eff, void* stream);
+
+/* Approximate attention (Figure 5, stage 2): ordinary softmax attention of q
+ * over the valid tokens of the listed pages only,
+ *   out[b][h][:] = sum_j softmax_j(sm_scale * q.k_j) * v_j,
+ *   lse[b][h]    = log sum_j exp(sm_scale * q.k_j)            (nullable).
+ * topk_idx rows are read up to min(k_pages, P_b) entries and stop at the first
+ * negative id.  topk_idx == NULL selects every page: the dense baseline
+ * (k_pages is then ignored).  fp16 inputs, fp32 dot products, fp32 online
+ * softmax over splits of the page list, merged in a second pass.  out is fp32
+ * if out_is_fp16 == 0, else fp16 (rounded once, from the fp32 result).
+ * workspace: at least quest_workspace_bytes(cache, topk_idx ? k_pages : 0). */
+int quest_sparse_decode(const quest_cache* cache, const void* q, const int32_t* topk_idx,
+                        int32_t k_pages, float sm_scale, void* out, int32_t out_is_fp16,
+                        float* lse, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Human-readable description of the last error on the calling thread.  Host
+ * string owned by the library, valid until the thread's next failing call. */
+const char* quest_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QUEST_H_ */

@@ -1,0 +1,120 @@
+// Shared device helpers and host-side launch plumbing for the Quest kernels.
+// gfx950 only: 64-lane wavefronts, DPP row operations, packed 16-bit integer
+// min/max, v_dot2_f32_f16.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/quest.h"
+
+namespace quest {
+
+constexpr int kHeadDim = 128;   // D: channels per head
+constexpr int kPageSize = 16;   // S: tokens per page
+constexpr int kWave = 64;
+// One (page, head) block of keys (or of values) is S*D fp16 = 4 KiB = 4 wave-wide
+// 16-byte loads; one metadata entry (min row + max row) is 512 B.
+constexpr int kBlockBytes = kPageSize * kHeadDim * 2;
+constexpr int kMetaBytes = 2 * kHeadDim * 2;
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef short short2_t __attribute__((ext_vector_type(2)));
+
+// ---------------------------------------------------------------- host side
+void set_error(const char* fmt, ...);
+int check_cache(const quest_cache* c, const char* who);
+int check_launch(const char* who);
+
+// Launchers (one per kernel family); each validates nothing, quest_api.hip does.
+int launch_build_meta(const quest_cache& c, hipStream_t s);
+int launch_append_meta(const quest_cache& c, const void* k_new, const void* v_new,
+                       int k_pool_write, hipStream_t s);
+int launch_estimate(const quest_cache& c, const void* q, float* scores, hipStream_t s);
+int launch_topk(const quest_cache& c, const float* scores, int k_pages, int32_t* topk_idx,
+                int32_t* k_eff, hipStream_t s);
+int decode_num_splits(const quest_cache& c, int k_pages);
+size_t decode_workspace_bytes(const quest_cache& c, int k_pages);
+int launch_sparse_decode(const quest_cache& c, const void* q, const int32_t* topk_idx, int k_pages,
+                         float sm_scale, void* out, int out_is_fp16, float* lse, void* workspace,
+                         hipStream_t s);
+
+// -------------------------------------------------------------- device side
+#if defined(__HIPCC__)
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
+
+// 16-byte global load / store (global_load_dwordx4).
+__device__ __forceinline__ uint4 ld16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
+__device__ __forceinline__ void st16(void* p, uint4 v) { *reinterpret_cast<uint4*>(p) = v; }
+
+// x + (x rotated right by N lanes inside its 16-lane DPP row).
+template <int N>
+__device__ __forceinline__ float row_ror_add(float x) {
+  int v = __builtin_bit_cast(int, x);
+  v = __builtin_amdgcn_update_dpp(0, v, 0x120 + N, 0xf, 0xf, false);
+  return x + __builtin_bit_cast(float, v);
+}
+
+// Sum over the 16 lanes of a DPP row; every lane of the row gets the same bits
+// (rotations by 8, 4, 2, 1: each step adds two already-identical partial sums
+// in commuted order, so the result does not depend on the lane).
+__device__ __forceinline__ float row16_sum(float x) {
+  x = row_ror_add<8>(x);
+  x = row_ror_add<4>(x);
+  x = row_ror_add<2>(x);
+  x = row_ror_add<1>(x);
+  return x;
+}
+
+// fp16 pair dot product accumulated in fp32 (v_dot2_f32_f16).
+__device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float acc) {
+  return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, a), __builtin_bit_cast(half2_t, b), acc,
+                                false);
+}
+
+// 8-channel fp16 dot product of two 16-byte vectors, fp32 accumulate.
+__device__ __forceinline__ float dot8(uint4 a, uint4 b, float acc) {
+  acc = dot2(a.x, b.x, acc);
+  acc = dot2(a.y, b.y, acc);
+  acc = dot2(a.z, b.z, acc);
+  acc = dot2(a.w, b.w, acc);
+  return acc;
+}
+
+// fp16 bit pattern <-> signed 16-bit key whose integer order is "by value,
+// -0 below +0": non-negative halves map to themselves, negative ones get their
+// magnitude bits flipped.  The map is its own inverse.  Two halves per dword.
+__device__ __forceinline__ uint32_t order_key2(uint32_t h2) {
+  short2_t v = __builtin_bit_cast(short2_t, h2);
+  v = v ^ ((v >> 15) & (short)0x7fff);
+  return __builtin_bit_cast(uint32_t, v);
+}
+__device__ __forceinline__ uint32_t key_min2(uint32_t a, uint32_t b) {
+  return __builtin_bit_cast(
+      uint32_t, __builtin_elementwise_min(__builtin_bit_cast(short2_t, a), __builtin_bit_cast(short2_t, b)));
+}
+__device__ __forceinline__ uint32_t key_max2(uint32_t a, uint32_t b) {
+  return __builtin_bit_cast(
+      uint32_t, __builtin_elementwise_max(__builtin_bit_cast(short2_t, a), __builtin_bit_cast(short2_t, b)));
+}
+__device__ __forceinline__ uint4 order_key8(uint4 v) {
+  return make_uint4(order_key2(v.x), order_key2(v.y), order_key2(v.z), order_key2(v.w));
+}
+__device__ __forceinline__ uint4 key_min8(uint4 a, uint4 b) {
+  return make_uint4(key_min2(a.x, b.x), key_min2(a.y, b.y), key_min2(a.z, b.z), key_min2(a.w, b.w));
+}
+__device__ __forceinline__ uint4 key_max8(uint4 a, uint4 b) {
+  return make_uint4(key_max2(a.x, b.x), key_max2(a.y, b.y), key_max2(a.z, b.z), key_max2(a.w, b.w));
+}
+
+__device__ __forceinline__ uint4 shfl_xor16(uint4 v, int mask) {
+  return make_uint4(__shfl_xor(v.x, mask), __shfl_xor(v.y, mask), __shfl_xor(v.z, mask),
+                    __shfl_xor(v.w, mask));
+}
+
+__device__ __forceinline__ int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+#endif  // __HIPCC__
+
+}  // namespace quest

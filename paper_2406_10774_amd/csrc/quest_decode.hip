@@ -1,0 +1,300 @@
+// Sparse paged decode attention (Figure 5 stage 2 / Section 3.4 of arXiv
+// 2406.10774): ordinary softmax attention of one query per (sequence, head)
+// over the tokens of the selected pages only.  With no page list it runs over
+// every page: the dense baseline the paper compares against (Section 3.1).
+//
+// Split-K flash-decoding.  Grid = (split, head, sequence); each work-group of
+// four waves owns a contiguous slice of the head's page list, its waves take
+// the slice's pages round-robin.  A wave streams one (page, head) block of
+// keys and one of values per step (4 KiB each = 4 wave-wide 16-byte loads
+// each), double-buffered in registers so the next page's eight loads are in
+// flight while the current page is reduced.  Lane l holds channels
+// 8*(l%16)..+7 of tokens l/16 + 4r; q.k is a v_dot2_f32_f16 chain plus a
+// reduction inside the 16-lane DPP row; each DPP row keeps its own online
+// softmax state (running max, denominator, 8 accumulator channels per lane) in
+// fp32, in the log2 domain.  Rows, waves and finally splits are merged with the
+// usual (max, sum, accumulator) rescaling; the split merge is a second kernel.
+//
+// Single-query attention is a matrix-vector product (about one flop per byte
+// read), far below the machine balance, so there is no MFMA here: the kernel is
+// bound by how fast HBM delivers the 8 KiB per selected (page, head).
+#include "quest_common.h"
+
+#include <cmath>
+#include <cstdlib>
+
+namespace quest {
+
+namespace {
+
+constexpr int kDecWaves = 4;
+constexpr int kDecThreads = kDecWaves * kWave;
+constexpr float kNegBig = -1.0e30f;  // "no token yet": finite, so exp2(m - m) never sees inf - inf
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+struct DecodeArgs {
+  const char* k_pool;
+  const char* v_pool;
+  const char* q;
+  const int32_t* page_table;
+  const int32_t* seq_lens;
+  const int32_t* topk_idx;  // nullptr: all pages
+  float* part_acc;          // [B*H*splits][D]   un-normalised accumulators
+  float* part_ml;           // [B*H*splits][2]   running max (log2 domain), denominator
+  void* out;
+  float* lse;
+  int num_heads, max_pages, k_pages, splits, out_is_fp16;
+  float scale_log2;  // sm_scale * log2(e)
+};
+
+struct PageRegs {
+  uint4 k[4], v[4];
+  int n_valid;
+};
+
+__device__ __forceinline__ float lo(uint32_t h2) {
+  return (float)__builtin_bit_cast(half2_t, h2)[0];
+}
+__device__ __forceinline__ float hi(uint32_t h2) {
+  return (float)__builtin_bit_cast(half2_t, h2)[1];
+}
+
+struct Softmax {
+  float m, l, acc[8];
+};
+
+__device__ __forceinline__ void load_page(PageRegs& r, const DecodeArgs& a, int h, int seq_len,
+                                          int logical_page, int phys, int lane) {
+  const size_t off = ((size_t)phys * a.num_heads + h) * kBlockBytes + lane * 16;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) r.k[i] = ld16(a.k_pool + off + i * 1024);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) r.v[i] = ld16(a.v_pool + off + i * 1024);
+  r.n_valid = min(kPageSize, seq_len - logical_page * kPageSize);
+}
+
+__device__ __forceinline__ void fold_page(Softmax& st, PageRegs& r, const uint4 qv, float scale_log2,
+                                          int grp) {
+  float z[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) z[i] = row16_sum(dot8(qv, r.k[i], 0.f)) * scale_log2;
+  if (r.n_valid < kPageSize) {  // partial last page: stale slots contribute nothing
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (grp + 4 * i >= r.n_valid) {
+        z[i] = -INFINITY;
+        r.v[i] = make_uint4(0, 0, 0, 0);
+      }
+    }
+  }
+  const float m_new = fmaxf(fmaxf(st.m, fmaxf(z[0], z[1])), fmaxf(z[2], z[3]));
+  const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
+  float p[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) p[i] = __builtin_amdgcn_exp2f(z[i] - m_new);
+  st.l = st.l * alpha + ((p[0] + p[1]) + (p[2] + p[3]));
+#pragma unroll
+  for (int j = 0; j < 8; ++j) st.acc[j] *= alpha;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    st.acc[0] += p[i] * lo(r.v[i].x);
+    st.acc[1] += p[i] * hi(r.v[i].x);
+    st.acc[2] += p[i] * lo(r.v[i].y);
+    st.acc[3] += p[i] * hi(r.v[i].y);
+    st.acc[4] += p[i] * lo(r.v[i].z);
+    st.acc[5] += p[i] * hi(r.v[i].z);
+    st.acc[6] += p[i] * lo(r.v[i].w);
+    st.acc[7] += p[i] * hi(r.v[i].w);
+  }
+  st.m = m_new;
+}
+
+// merge the state held by lane ^ mask into this lane's
+__device__ __forceinline__ void merge_lanes(Softmax& st, int mask) {
+  const float m_o = __shfl_xor(st.m, mask);
+  const float l_o = __shfl_xor(st.l, mask);
+  const float m_n = fmaxf(st.m, m_o);
+  const float a = __builtin_amdgcn_exp2f(st.m - m_n);
+  const float b = __builtin_amdgcn_exp2f(m_o - m_n);
+  st.l = st.l * a + l_o * b;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) st.acc[j] = st.acc[j] * a + __shfl_xor(st.acc[j], mask) * b;
+  st.m = m_n;
+}
+
+__device__ __forceinline__ void store_out(void* out, int out_is_fp16, size_t idx, float v) {
+  if (out_is_fp16)
+    reinterpret_cast<_Float16*>(out)[idx] = (_Float16)v;
+  else
+    reinterpret_cast<float*>(out)[idx] = v;
+}
+
+__global__ __launch_bounds__(kDecThreads) void decode_split_kernel(const DecodeArgs a) {
+  __shared__ float sm_acc[kDecWaves][kHeadDim];
+  __shared__ float sm_m[kDecWaves], sm_l[kDecWaves];
+
+  const int split = blockIdx.x;
+  const int h = blockIdx.y;
+  const int b = blockIdx.z;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = lane_id();
+  const int grp = lane >> 4;
+  const int c = lane & 15;
+  const size_t bh = (size_t)b * a.num_heads + h;
+
+  const int seq_len = a.seq_lens[b];
+  const int num_pages = (seq_len + kPageSize - 1) / kPageSize;
+  const int n_sel = a.topk_idx ? min(a.k_pages, num_pages) : num_pages;
+  const int per_split = (n_sel + a.splits - 1) / a.splits;
+  const int begin = split * per_split;
+  const int end = min(n_sel, begin + per_split);
+  const int32_t* idx_row = a.topk_idx ? a.topk_idx + bh * a.k_pages : nullptr;
+  const int32_t* pt = a.page_table + (size_t)b * a.max_pages;
+
+  const uint4 qv = ld16(a.q + bh * (kHeadDim * 2) + c * 16);
+
+  Softmax st;
+  st.m = kNegBig;
+  st.l = 0.f;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) st.acc[j] = 0.f;
+
+  // logical page at list position pos, or -1 past the end of this wave's share
+  auto page_at = [&](int pos) -> int {
+    if (pos >= end) return -1;
+    return idx_row ? idx_row[pos] : pos;
+  };
+
+  PageRegs ra, rb;
+  int pos = begin + wave;
+  int lp = page_at(pos);
+  if (lp >= 0) load_page(ra, a, h, seq_len, lp, pt[lp], lane);
+  while (lp >= 0) {
+    int lp_b = page_at(pos + kDecWaves);
+    if (lp_b >= 0) load_page(rb, a, h, seq_len, lp_b, pt[lp_b], lane);
+    fold_page(st, ra, qv, a.scale_log2, grp);
+    if (lp_b < 0) break;
+    pos += 2 * kDecWaves;
+    lp = page_at(pos);
+    if (lp >= 0) load_page(ra, a, h, seq_len, lp, pt[lp], lane);
+    fold_page(st, rb, qv, a.scale_log2, grp);
+  }
+
+  // the four DPP rows of the wave, then the four waves of the group
+  merge_lanes(st, 16);
+  merge_lanes(st, 32);
+  if (lane < 16) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) sm_acc[wave][c * 8 + j] = st.acc[j];
+    if (lane == 0) {
+      sm_m[wave] = st.m;
+      sm_l[wave] = st.l;
+    }
+  }
+  __syncthreads();
+  const int t = threadIdx.x;
+  if (t < kHeadDim) {
+    float m_tot = sm_m[0];
+#pragma unroll
+    for (int w = 1; w < kDecWaves; ++w) m_tot = fmaxf(m_tot, sm_m[w]);
+    float l_tot = 0.f, acc = 0.f;
+#pragma unroll
+    for (int w = 0; w < kDecWaves; ++w) {
+      const float f = __builtin_amdgcn_exp2f(sm_m[w] - m_tot);
+      l_tot += sm_l[w] * f;
+      acc += sm_acc[w][t] * f;
+    }
+    if (a.splits == 1) {
+      store_out(a.out, a.out_is_fp16, bh * kHeadDim + t, acc / l_tot);
+      if (t == 0 && a.lse) a.lse[bh] = (m_tot + __builtin_amdgcn_logf(l_tot)) * kLn2;
+    } else {
+      const size_t ps = bh * a.splits + split;
+      a.part_acc[ps * kHeadDim + t] = acc;
+      if (t == 0) {
+        a.part_ml[ps * 2 + 0] = m_tot;
+        a.part_ml[ps * 2 + 1] = l_tot;
+      }
+    }
+  }
+}
+
+// Second pass: one work-group per (sequence, head), thread t = output channel.
+__global__ __launch_bounds__(kHeadDim) void decode_merge_kernel(const DecodeArgs a) {
+  const int h = blockIdx.x;
+  const int b = blockIdx.y;
+  const int t = threadIdx.x;
+  const size_t bh = (size_t)b * a.num_heads + h;
+  const float* ml = a.part_ml + bh * a.splits * 2;
+  const float* pacc = a.part_acc + bh * a.splits * kHeadDim;
+  float m_tot = kNegBig;
+  for (int s = 0; s < a.splits; ++s) m_tot = fmaxf(m_tot, ml[2 * s]);
+  float l_tot = 0.f, acc = 0.f;
+  for (int s = 0; s < a.splits; ++s) {
+    const float f = __builtin_amdgcn_exp2f(ml[2 * s] - m_tot);
+    l_tot += ml[2 * s + 1] * f;
+    acc += pacc[(size_t)s * kHeadDim + t] * f;
+  }
+  store_out(a.out, a.out_is_fp16, bh * kHeadDim + t, acc / l_tot);
+  if (t == 0 && a.lse) a.lse[bh] = (m_tot + __builtin_amdgcn_logf(l_tot)) * kLn2;
+}
+
+int env_int(const char* name, int fallback) {
+  const char* v = std::getenv(name);
+  return (v && *v) ? std::atoi(v) : fallback;
+}
+
+}  // namespace
+
+// Number of splits of a head's page list.  Sized so that a split holds about
+// eight pages (two per wave: both in flight at once) while the whole launch
+// stays within a few thousand work-groups.
+int decode_num_splits(const quest_cache& c, int k_pages) {
+  static const int pages_per_split = env_int("QUEST_DECODE_PAGES_PER_SPLIT", 8);
+  static const int max_groups = env_int("QUEST_DECODE_MAX_GROUPS", 8192);
+  const int n_sel = k_pages > 0 ? (k_pages < c.max_pages_per_seq ? k_pages : c.max_pages_per_seq)
+                                : c.max_pages_per_seq;
+  const long bh = (long)c.batch * c.num_heads;
+  long splits = (n_sel + pages_per_split - 1) / pages_per_split;
+  const long cap = max_groups / bh > 0 ? max_groups / bh : 1;
+  if (splits > cap) splits = cap;
+  if (splits < 1) splits = 1;
+  return (int)splits;
+}
+
+size_t decode_workspace_bytes(const quest_cache& c, int k_pages) {
+  const size_t splits = decode_num_splits(c, k_pages);
+  if (splits == 1) return 0;
+  return (size_t)c.batch * c.num_heads * splits * (kHeadDim + 2) * sizeof(float);
+}
+
+int launch_sparse_decode(const quest_cache& c, const void* q, const int32_t* topk_idx, int k_pages,
+                         float sm_scale, void* out, int out_is_fp16, float* lse, void* workspace,
+                         hipStream_t s) {
+  DecodeArgs a;
+  a.k_pool = (const char*)c.k_pool;
+  a.v_pool = (const char*)c.v_pool;
+  a.q = (const char*)q;
+  a.page_table = c.page_table;
+  a.seq_lens = c.seq_lens;
+  a.topk_idx = topk_idx;
+  a.num_heads = c.num_heads;
+  a.max_pages = c.max_pages_per_seq;
+  a.k_pages = topk_idx ? k_pages : 0;
+  a.splits = decode_num_splits(c, a.k_pages);
+  a.out = out;
+  a.out_is_fp16 = out_is_fp16;
+  a.lse = lse;
+  a.scale_log2 = sm_scale * kLog2e;
+  const size_t n_part = (size_t)c.batch * c.num_heads * a.splits;
+  a.part_acc = (float*)workspace;
+  a.part_ml = a.part_acc ? a.part_acc + n_part * kHeadDim : nullptr;
+  hipLaunchKernelGGL(decode_split_kernel, dim3(a.splits, c.num_heads, c.batch), dim3(kDecThreads), 0,
+                     s, a);
+  int r = check_launch("quest_sparse_decode (split pass)");
+  if (r != QUEST_OK || a.splits == 1) return r;
+  hipLaunchKernelGGL(decode_merge_kernel, dim3(c.num_heads, c.batch), dim3(kHeadDim), 0, s, a);
+  return check_launch("quest_sparse_decode (merge pass)");
+}
+
+}  // namespace quest

@@ -1,0 +1,134 @@
+// Per-page channel-wise min/max key metadata: bulk build after prefill and the
+// per-token update (Section 3.4 and the insertion half of Algorithm 1 of
+// arXiv 2406.10774).
+//
+// Both kernels compare fp16 values through a signed 16-bit key whose integer
+// order is "by value, -0 below +0" (order_key2), with packed 16-bit min/max.
+// Integer min/max are associative and commutative, so any reduction tree gives
+// the same bits as a sequential scan.
+#include "quest_common.h"
+
+namespace quest {
+
+namespace {
+
+constexpr int kBuildWaves = 4;          // waves per work-group
+constexpr int kBuildPagesPerWave = 4;   // (page, head) key blocks per wave, all loads issued up front
+constexpr int kBuildPagesPerGroup = kBuildWaves * kBuildPagesPerWave;
+
+constexpr uint32_t kKeyMax2 = 0x7fff7fffu;  // identity of min
+constexpr uint32_t kKeyMin2 = 0x80008000u;  // identity of max
+
+// One wave reduces one 4 KiB key block.  Lane l holds channels 8*(l%16)..+7 of
+// tokens l/16 + 4r (r = 0..3): load r of the wave is the contiguous 1 KiB
+// [r*1024, r*1024+1024) of the block, 16 bytes per lane.
+__global__ __launch_bounds__(kBuildWaves* kWave) void build_meta_kernel(
+    const char* __restrict__ k_pool, char* __restrict__ meta, const int32_t* __restrict__ page_table,
+    const int32_t* __restrict__ seq_lens, int num_heads, int max_pages) {
+  const int b = blockIdx.z;
+  const int h = blockIdx.y;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = lane_id();
+  const int grp = lane >> 4;
+  const int seq_len = seq_lens[b];
+  const int num_pages = (seq_len + kPageSize - 1) / kPageSize;
+  const int page0 = (blockIdx.x * kBuildWaves + wave) * kBuildPagesPerWave;
+  if (page0 >= num_pages) return;
+
+  uint4 buf[kBuildPagesPerWave][4];
+  int phys[kBuildPagesPerWave];
+#pragma unroll
+  for (int u = 0; u < kBuildPagesPerWave; ++u) {
+    const int p = page0 + u;
+    if (p < num_pages) {
+      phys[u] = page_table[(size_t)b * max_pages + p];
+      const char* blk = k_pool + ((size_t)phys[u] * num_heads + h) * kBlockBytes;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) buf[u][r] = ld16(blk + r * 1024 + lane * 16);
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < kBuildPagesPerWave; ++u) {
+    const int p = page0 + u;
+    if (p >= num_pages) break;
+    const int n_valid = min(kPageSize, seq_len - p * kPageSize);
+    uint4 mn = make_uint4(kKeyMax2, kKeyMax2, kKeyMax2, kKeyMax2);
+    uint4 mx = make_uint4(kKeyMin2, kKeyMin2, kKeyMin2, kKeyMin2);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      if (grp + 4 * r < n_valid) {  // stale slots of a partial page never take part
+        const uint4 key = order_key8(buf[u][r]);
+        mn = key_min8(mn, key);
+        mx = key_max8(mx, key);
+      }
+    }
+    // combine the four 16-lane groups (tokens s%4 == 0,1,2,3)
+    mn = key_min8(mn, shfl_xor16(mn, 16));
+    mx = key_max8(mx, shfl_xor16(mx, 16));
+    mn = key_min8(mn, shfl_xor16(mn, 32));
+    mx = key_max8(mx, shfl_xor16(mx, 32));
+    // lanes 0..15 store the min row, lanes 16..31 the max row: 512 contiguous bytes
+    char* entry = meta + ((size_t)phys[u] * num_heads + h) * kMetaBytes;
+    if (lane < 32) st16(entry + lane * 16, order_key8(grp == 0 ? mn : mx));
+  }
+}
+
+// 16 lanes per (sequence, head): lane c owns channels 8c..8c+7 of the new token.
+__global__ __launch_bounds__(256) void append_meta_kernel(
+    char* __restrict__ k_pool, char* __restrict__ v_pool, char* __restrict__ meta,
+    const int32_t* __restrict__ page_table, const int32_t* __restrict__ seq_lens,
+    const char* __restrict__ k_new, const char* __restrict__ v_new, int batch, int num_heads,
+    int max_pages, int k_pool_write) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  const int bh = t >> 4;
+  const int c = t & 15;
+  if (bh >= batch * num_heads) return;
+  const int b = bh / num_heads;
+  const int h = bh - b * num_heads;
+  const int pos = seq_lens[b] - 1;
+  const int page = pos / kPageSize;
+  const int slot = pos - page * kPageSize;
+  const int phys = page_table[(size_t)b * max_pages + page];
+  const size_t ph = (size_t)phys * num_heads + h;
+
+  const uint4 k = ld16(k_new + (size_t)bh * (kHeadDim * 2) + c * 16);
+  if (k_pool_write) {
+    const size_t off = ph * kBlockBytes + (size_t)slot * (kHeadDim * 2) + c * 16;
+    st16(k_pool + off, k);
+    st16(v_pool + off, ld16(v_new + (size_t)bh * (kHeadDim * 2) + c * 16));
+  }
+  char* entry = meta + ph * kMetaBytes + c * 16;
+  if (slot == 0) {  // first token of a page: min = max = k
+    st16(entry, k);
+    st16(entry + kHeadDim * 2, k);
+  } else {
+    const uint4 key = order_key8(k);
+    const uint4 mn = key_min8(order_key8(ld16(entry)), key);
+    const uint4 mx = key_max8(order_key8(ld16(entry + kHeadDim * 2)), key);
+    st16(entry, order_key8(mn));
+    st16(entry + kHeadDim * 2, order_key8(mx));
+  }
+}
+
+}  // namespace
+
+int launch_build_meta(const quest_cache& c, hipStream_t s) {
+  dim3 grid((c.max_pages_per_seq + kBuildPagesPerGroup - 1) / kBuildPagesPerGroup, c.num_heads,
+            c.batch);
+  hipLaunchKernelGGL(build_meta_kernel, grid, dim3(kBuildWaves * kWave), 0, s,
+                     (const char*)c.k_pool, (char*)c.meta, c.page_table, c.seq_lens, c.num_heads,
+                     c.max_pages_per_seq);
+  return check_launch("quest_build_meta");
+}
+
+int launch_append_meta(const quest_cache& c, const void* k_new, const void* v_new, int k_pool_write,
+                       hipStream_t s) {
+  const int threads = c.batch * c.num_heads * 16;
+  hipLaunchKernelGGL(append_meta_kernel, dim3((threads + 255) / 256), dim3(256), 0, s,
+                     (char*)c.k_pool, (char*)c.v_pool, (char*)c.meta, c.page_table, c.seq_lens,
+                     (const char*)k_new, (const char*)v_new, c.batch, c.num_heads,
+                     c.max_pages_per_seq, k_pool_write);
+  return check_launch("quest_append_meta");
+}
+
+}  // namespace quest

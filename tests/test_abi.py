@@ -1,0 +1,89 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports
+every function include/quest.h declares, and rejects bad arguments with the
+documented status codes before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2406_10774_amd import binding
+
+
+def declared_functions(repo_root):
+    text = open(os.path.join(repo_root, "include", "quest.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(quest_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(repo_root):
+    lib = binding.load()
+    names = declared_functions(repo_root)
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def make_cache(**kw):
+    base = dict(batch=1, num_heads=32, head_dim=128, page_size=16, max_pages_per_seq=2048,
+                reserved=0, num_phys_pages=2048, k_pool=0x1000, v_pool=0x1000, meta=0x1000,
+                page_table=0x1000, seq_lens=0x1000)
+    base.update(kw)
+    return binding.quest_cache(**base)
+
+
+def test_workspace_bytes_is_pure_and_consistent():
+    lib = binding.load()
+    out = ctypes.c_size_t(0)
+    c = make_cache()
+    assert lib.quest_workspace_bytes(ctypes.byref(c), 128, ctypes.byref(out)) == 0
+    sparse = out.value
+    assert lib.quest_workspace_bytes(ctypes.byref(c), 0, ctypes.byref(out)) == 0
+    dense = out.value
+    # partials: (D + 2) floats per (head, split); dense path uses at least as many splits
+    assert sparse % (32 * 130 * 4) == 0 and dense % (32 * 130 * 4) == 0
+    assert dense >= sparse > 0
+    assert lib.quest_workspace_bytes(ctypes.byref(c), 128, None) == -1
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(head_dim=64), -3), (dict(page_size=32), -3), (dict(batch=0), -2),
+    (dict(num_heads=70000), -2), (dict(page_table=None), -1), (dict(seq_lens=None), -1),
+    (dict(max_pages_per_seq=0), -2),
+])
+def test_bad_cache_is_rejected_on_the_host(kw, status):
+    lib = binding.load()
+    c = make_cache(**kw)
+    assert lib.quest_build_meta(ctypes.byref(c), None) == status
+    assert lib.quest_estimate(ctypes.byref(c), 0x1000, 0x1000, None) == status
+    assert lib.quest_last_error()          # a message is available
+
+
+def test_null_and_range_arguments():
+    lib = binding.load()
+    c = make_cache()
+    r = ctypes.byref(c)
+    assert lib.quest_build_meta(None, None) == -1
+    assert lib.quest_estimate(r, None, 0x1000, None) == -1
+    assert lib.quest_estimate(r, 0x1000, None, None) == -1
+    assert lib.quest_append_meta(r, None, None, 0, None) == -1
+    assert lib.quest_append_meta(r, 0x1000, None, 1, None) == -1     # pool write needs v_new
+    assert lib.quest_topk(r, 0x1000, 0, 0x1000, None, None) == -2    # k_pages < 1
+    assert lib.quest_topk(r, None, 4, 0x1000, None, None) == -1
+    assert lib.quest_sparse_decode(r, 0x1000, 0x1000, 0, 1.0, 0x1000, 0, None, 0x1000, 1 << 30,
+                                   None) == -2
+    # workspace too small / missing
+    assert lib.quest_sparse_decode(r, 0x1000, 0x1000, 128, 1.0, 0x1000, 0, None, 0x1000, 16,
+                                   None) == -4
+    assert lib.quest_sparse_decode(r, 0x1000, 0x1000, 128, 1.0, 0x1000, 0, None, None, 0,
+                                   None) == -4
+    assert b"workspace" in lib.quest_last_error()
+
+
+def test_product_package_does_not_import_the_oracle(repo_root):
+    pkg = os.path.join(repo_root, "paper_2406_10774_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in src.replace("the CPU oracle's tests", ""), f

@@ -1,0 +1,79 @@
+"""GPU parity of the whole decode step (append -> estimate -> top-k -> sparse
+attention) chained on the device, against the oracle chained on the CPU, on the
+benchmark configurations: config 0 (tiny) and config 1 at its full size
+(32 heads, 32k context, budget 2048) in the launch configuration the benchmark
+times, plus the dense (all pages) path on the same buffers."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import quest_oracle as O
+from paper_2406_10774_amd import synth
+
+pytestmark = pytest.mark.gpu
+ATTN_TOL = 2e-3
+
+
+def run_chain(w, steps, permute):
+    from gpu_util import Layer, check_selection, score_tolerance
+    S, D = w.page_size, w.head_dim
+    table, N = synth.make_page_table(w, permute=permute)
+    k_pool, v_pool, q0 = synth.fill_pools(w, table, N)
+    lens = np.array(w.seq_lens, np.int32)
+    layer = Layer(k_pool, v_pool, table, lens)
+    scale = 1 / math.sqrt(D)
+
+    meta = O.build_meta(k_pool, table, lens)
+    got_meta = layer.build_meta()
+    mapped = np.unique(np.concatenate([table[b, :w.pages_of(b)] for b in range(w.batch)]))
+    assert np.array_equal(got_meta[mapped].view(np.uint16), meta[mapped].view(np.uint16))
+
+    cur = lens.copy()
+    near_ties = 0
+    for step in range(steps):
+        q = synth.gen_query(w, step)
+        if step > 0:                                   # append one token, then attend
+            k_new, v_new = synth.gen_new_token(w, step)
+            cur += 1
+            layer.set_seq_lens(cur)
+            layer.append(k_new, v_new, write=True)
+            O.append_kv(k_pool, v_pool, k_new, v_new, table, cur)
+            meta = O.append_meta(meta, k_new, table, cur, S)
+        sc = O.estimate(meta, q, table, cur, S)
+        got_sc = layer.estimate(q)
+        tol = score_tolerance(meta, q, table, cur, S)
+        for b in range(w.batch):
+            P = -(-int(cur[b]) // S)
+            assert (np.abs(got_sc[b, :, :P] - sc[b, :, :P]) <= tol[b, :, :P]).all(), step
+        got_idx, keff = layer.topk(w.k_pages)          # from the GPU's own fp32 scores
+        near_ties += check_selection(got_idx, sc, cur, S, w.k_pages)
+        # attention over the pages the GPU chose, against the oracle on the same pages
+        want, want_lse = O.sparse_decode(k_pool, v_pool, q, table, cur, got_idx, scale)
+        got, lse = layer.decode(q, got_idx, w.k_pages)
+        assert np.abs(got - want).max() <= ATTN_TOL, step
+        assert np.abs(lse - want_lse).max() <= ATTN_TOL, step
+    # metadata maintained over the steps == oracle's == rebuilt
+    got_meta = layer.np16(layer.meta)
+    mapped = np.unique(np.concatenate([table[b, :-(-int(cur[b]) // S)] for b in range(w.batch)]))
+    assert np.array_equal(got_meta[mapped].view(np.uint16), meta[mapped].view(np.uint16))
+    # dense path on the same buffers
+    q = synth.gen_query(w, 0)
+    want, want_lse = O.sparse_decode(k_pool, v_pool, q, table, cur, None, scale)
+    got, lse = layer.decode(q, None, 0)
+    assert np.abs(got - want).max() <= ATTN_TOL
+    assert np.abs(lse - want_lse).max() <= ATTN_TOL
+    return near_ties
+
+
+def test_config0_chain():
+    run_chain(synth.workload(0), steps=5, permute=True)
+
+
+def test_config1_full_size_chain_identity_table():
+    """Same launch configuration as the benchmark (identity page table)."""
+    run_chain(synth.workload(1), steps=3, permute=False)
+
+
+def test_config1_full_size_chain_shuffled_pages():
+    run_chain(synth.workload(1), steps=18, permute=True)   # step 17 opens nothing new, 1..16 fill page 2048

@@ -1,0 +1,260 @@
+"""GPU parity, kernel by kernel: each HIP entry point is fed the oracle's
+upstream values and compared element by element with the CPU oracle on seeded
+inputs that span several tiles, a ragged batch, partial last pages and a
+shuffled page table.  Bars: metadata and page indices bit-exact; scores within
+the fp32 accumulation bound; attention within 2e-3 max-abs (fp32 store)."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import quest_oracle as O
+from paper_2406_10774_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+ATTN_TOL = 2e-3
+
+
+@pytest.fixture(scope="module")
+def ragged():
+    """B=4, H=5: lengths 1 token, a partial page, several tiles + tail, an exact multiple."""
+    from gpu_util import Layer
+    w = synth.Workload(90, "ragged-small", 4, 5, (1, 16 * 3 + 7, 16 * 203 + 5, 16 * 64),
+                       token_budget=16 * 24, planted_per_head=4, decode_steps=40)
+    table, N = synth.make_page_table(w, permute=True, spare_pages=3)
+    k_pool, v_pool, q = synth.fill_pools(w, table, N)
+    lens = np.array(w.seq_lens, np.int32)
+    layer = Layer(k_pool, v_pool, table, lens, meta_fill=77.0)
+    return w, table, N, k_pool, v_pool, q, lens, layer
+
+
+def test_build_meta_bit_exact(ragged):
+    w, table, N, k_pool, v_pool, q, lens, layer = ragged
+    # signed zeros inside valid slots
+    rng = np.random.default_rng(1)
+    k2 = k_pool.copy()
+    flat = k2.reshape(-1)
+    pick = rng.integers(0, flat.size, 20000)
+    flat[pick[:10000]] = np.float16(0.0)
+    flat[pick[10000:]] = np.float16(-0.0)
+    stale = np.isnan(k_pool)
+    k2[stale] = np.float16("nan")
+    layer.k_pool.copy_(layer.half(k2))
+    got = layer.build_meta()
+    want = O.build_meta(k2, table, lens, meta_init=np.full((N, w.num_heads, 2, w.head_dim), 77.0,
+                                                           np.float16))
+    assert np.array_equal(got.view(np.uint16), want.view(np.uint16))
+    layer.k_pool.copy_(layer.half(k_pool))
+    got = layer.build_meta()
+    want = O.build_meta(k_pool, table, lens, meta_init=np.full_like(want, 77.0))
+    assert np.array_equal(got.view(np.uint16), want.view(np.uint16))
+
+
+def test_append_meta_and_kv_write_bit_exact(ragged):
+    w, table, N, k_pool, v_pool, q, lens, layer = ragged
+    kp, vp = k_pool.copy(), v_pool.copy()
+    layer.k_pool.copy_(layer.half(kp))
+    layer.v_pool.copy_(layer.half(vp))
+    layer.set_seq_lens(lens)
+    meta = O.build_meta(kp, table, lens, meta_init=np.full((N, w.num_heads, 2, w.head_dim), 77.0,
+                                                           np.float16))
+    layer.build_meta()
+    cur = lens.copy()
+    rng = np.random.default_rng(3)
+    for step in range(w.decode_steps):          # crosses page boundaries for every sequence
+        k_new, v_new = synth.gen_new_token(w, step)
+        if step % 5 == 0:                       # ties and signed zeros
+            k_new = np.round(k_new).astype(np.float16)
+            k_new[k_new == 0] = rng.choice([np.float16(0.0), np.float16(-0.0)], (k_new == 0).sum())
+        cur += 1
+        layer.set_seq_lens(cur)
+        layer.append(k_new, v_new, write=True)
+        O.append_kv(kp, vp, k_new, v_new, table, cur)
+        meta = O.append_meta(meta, k_new, table, cur, w.page_size)
+    got = layer.np16(layer.meta)
+    assert np.array_equal(got.view(np.uint16), meta.view(np.uint16))
+    assert np.array_equal(layer.np16(layer.k_pool).view(np.uint16), kp.view(np.uint16))
+    assert np.array_equal(layer.np16(layer.v_pool).view(np.uint16), vp.view(np.uint16))
+    # rebuilding from the keys gives the incrementally maintained metadata
+    rebuilt = layer.build_meta()
+    assert np.array_equal(rebuilt.view(np.uint16), meta.view(np.uint16))
+    # append without pool write leaves the pools alone
+    cur += 1
+    layer.set_seq_lens(cur)
+    k_new, _ = synth.gen_new_token(w, 1000)
+    layer.append(k_new)
+    assert np.array_equal(layer.np16(layer.k_pool).view(np.uint16), kp.view(np.uint16))
+    meta = O.append_meta(meta, k_new, table, cur, w.page_size)
+    assert np.array_equal(layer.np16(layer.meta).view(np.uint16), meta.view(np.uint16))
+    # restore for the tests that follow
+    layer.k_pool.copy_(layer.half(k_pool))
+    layer.v_pool.copy_(layer.half(v_pool))
+    layer.set_seq_lens(lens)
+    layer.meta.fill_(77.0)
+    layer.build_meta()
+
+
+def test_estimate_within_fp32_bound(ragged):
+    w, table, N, k_pool, v_pool, q, lens, layer = ragged
+    meta = O.build_meta(k_pool, table, lens)
+    layer.build_meta()
+    for variant in range(3):
+        qq = [q, np.abs(q), (-np.abs(q)).astype(np.float16)][variant]
+        want = O.estimate(meta, qq, table, lens, w.page_size)
+        layer.scores.fill_(float("nan"))
+        got = layer.estimate(qq)
+        tol = score_tolerance_for(meta, qq, table, lens, w.page_size)
+        for b in range(w.batch):
+            P = w.pages_of(b)
+            assert np.isnan(got[b, :, P:]).all()            # padding entries are not written
+            err = np.abs(got[b, :, :P].astype(np.float64) - want[b, :, :P])
+            assert (err <= tol[b, :, :P]).all(), (variant, b, err.max())
+
+
+def score_tolerance_for(meta, q, table, lens, S):
+    from gpu_util import score_tolerance
+    return score_tolerance(meta, q, table, lens, S)
+
+
+@pytest.mark.parametrize("k_pages", [1, 3, 24, 64, 300])
+def test_topk_exact_on_shared_scores(ragged, k_pages):
+    w, table, N, k_pool, v_pool, q, lens, layer = ragged
+    rng = np.random.default_rng(k_pages)
+    sc = rng.standard_normal((w.batch, w.num_heads, layer.max_pages)).astype(np.float32) * 50
+    sc[:, 0] = np.round(sc[:, 0] / 25) * 25            # heavy ties
+    sc[:, 1] = 3.25                                    # all equal
+    sc[:, 2, ::2] = 0.0
+    sc[:, 2, 1::2] = -0.0                              # signed zeros rank equal
+    sc[:, 3] = -np.abs(sc[:, 3])                       # all negative
+    for b in range(w.batch):
+        sc[b, :, w.pages_of(b):] = np.inf              # beyond P: must be ignored
+    want, want_keff = O.topk(sc, lens, w.page_size, k_pages)
+    got, keff = layer.topk(k_pages, scores=sc)
+    assert np.array_equal(keff, want_keff)
+    assert np.array_equal(got, want)
+
+
+def test_sparse_decode_against_oracle(ragged):
+    w, table, N, k_pool, v_pool, q, lens, layer = ragged
+    meta = O.build_meta(k_pool, table, lens)
+    sc = O.estimate(meta, q, table, lens, w.page_size)
+    scale = 1 / math.sqrt(w.head_dim)
+    for k_pages in (1, 5, 24, 64):
+        idx, _ = O.topk(sc, lens, w.page_size, k_pages)
+        want, want_lse = O.sparse_decode(k_pool, v_pool, q, table, lens, idx, scale)
+        got, lse = layer.decode(q, idx, k_pages)
+        assert np.abs(got - want).max() <= ATTN_TOL, k_pages
+        assert np.abs(lse - want_lse).max() <= ATTN_TOL
+        # reversed page list: same result
+        rev = np.full_like(idx, -1)
+        for b in range(w.batch):
+            K = min(k_pages, w.pages_of(b))
+            rev[b, :, :K] = idx[b, :, :K][:, ::-1]
+        got2, _ = layer.decode(q, rev, k_pages)
+        assert np.abs(got2 - want).max() <= ATTN_TOL
+    # fp16 store: within one fp16 ulp of the rounded oracle
+    idx, _ = O.topk(sc, lens, w.page_size, 24)
+    want, _ = O.sparse_decode(k_pool, v_pool, q, table, lens, idx, scale)
+    got16, _ = layer.decode(q, idx, 24, fp16_out=True, want_lse=False)
+    w16 = want.astype(np.float16)
+    ulp = np.maximum(np.abs(np.spacing(w16)).astype(np.float64), 2.0 ** -24)
+    assert (np.abs(got16.astype(np.float64) - w16.astype(np.float64)) <= ulp).all()
+
+
+def test_dense_path_is_dense_attention(ragged):
+    w, table, N, k_pool, v_pool, q, lens, layer = ragged
+    scale = 0.07
+    want, want_lse = O.sparse_decode(k_pool, v_pool, q, table, lens, None, scale)
+    got, lse = layer.decode(q, None, 0, sm_scale=scale)
+    assert np.abs(got - want).max() <= ATTN_TOL
+    assert np.abs(lse - want_lse).max() <= ATTN_TOL
+    # K >= P through the page list gives the same
+    k_pages = layer.max_pages
+    idx, _ = O.topk(np.zeros((w.batch, w.num_heads, layer.max_pages)), lens, w.page_size, k_pages)
+    got2, _ = layer.decode(q, idx, k_pages, sm_scale=scale)
+    assert np.abs(got2 - want).max() <= ATTN_TOL
+
+
+def test_degenerate_attention_cases():
+    from gpu_util import Layer
+    rng = np.random.default_rng(5)
+    H, S, D = 2, 16, 128
+    k_pool = rng.standard_normal((4, H, S, D)).astype(np.float16)
+    v_pool = rng.standard_normal((4, H, S, D)).astype(np.float16)
+    q = rng.standard_normal((1, H, D)).astype(np.float16)
+    table = np.array([[2, 0, 3, 1]], np.int32)
+    lens = np.array([33], np.int32)                    # page 2 holds a single token
+    k_pool[3, :, 1:] = np.float16("nan")
+    v_pool[3, :, 1:] = np.float16("nan")
+    layer = Layer(k_pool, v_pool, table, lens)
+    idx = np.array([[[2, -1], [2, -1]]], np.int32)
+    got, lse = layer.decode(q, idx, 2)
+    assert np.abs(got[0] - v_pool[3, :, 0].astype(np.float64)).max() <= 1e-6   # o = v
+    k_pool[:] = k_pool[0, 0, 0]                        # all keys equal -> mean of values
+    k_pool[3, :, 1:] = np.float16("nan")
+    layer = Layer(k_pool, v_pool, table, lens)
+    idx = np.array([[[0, 2], [1, 2]]], np.int32)
+    got, _ = layer.decode(q, idx, 2)
+    for h, first in enumerate((2, 0)):
+        want = np.concatenate([v_pool[first, h], v_pool[3, h, :1]]).astype(np.float64).mean(0)
+        assert np.abs(got[0, h] - want).max() <= 1e-5
+
+
+def test_every_kernel_is_deterministic(ragged):
+    w, table, N, k_pool, v_pool, q, lens, layer = ragged
+    layer.build_meta()
+    s1 = layer.estimate(q).copy()
+    s2 = layer.estimate(q)
+    assert np.array_equal(s1.view(np.uint32), s2.view(np.uint32))
+    i1, _ = layer.topk(24)
+    i2, _ = layer.topk(24)
+    assert np.array_equal(i1, i2)
+    o1, l1 = layer.decode(q, i1, 24)
+    o2, l2 = layer.decode(q, i1, 24)
+    assert np.array_equal(o1.view(np.uint32), o2.view(np.uint32))
+    assert np.array_equal(l1.view(np.uint32), l2.view(np.uint32))
+
+
+def test_offsets_beyond_4gib():
+    """Physical page ids near the top of a 6 GiB pool: byte offsets need 64 bits."""
+    import torch
+    from gpu_util import Layer
+    from paper_2406_10774_amd import binding as Q
+    H, S, D = 32, 16, 128
+    N = 49152                                           # 49152 * 128 KiB = 6 GiB per pool
+    w = synth.Workload(91, "high-pages", 1, H, (16 * 40 + 3,), 16 * 8, 2, decode_steps=0)
+    small_table, n_small = synth.make_page_table(w, permute=True, spare_pages=0)
+    k_s, v_s, q = synth.fill_pools(w, small_table, n_small)
+    lens = np.array(w.seq_lens, np.int32)
+    hi_ids = (N - 1 - np.arange(n_small) * 3).astype(np.int32)       # scattered, all > 4 GiB / 128 KiB
+    table = hi_ids[small_table]
+    dev = "cuda:0"
+    k_pool = torch.empty((N, H, S, D), dtype=torch.float16, device=dev)
+    v_pool = torch.empty((N, H, S, D), dtype=torch.float16, device=dev)
+    ids = torch.from_numpy(hi_ids.astype(np.int64)).to(dev)
+    k_pool[ids] = torch.from_numpy(k_s.view(np.int16)).to(dev).view(torch.float16)
+    v_pool[ids] = torch.from_numpy(v_s.view(np.int16)).to(dev).view(torch.float16)
+    meta = torch.zeros((N, H, 2, D), dtype=torch.float16, device=dev)
+    pt = torch.from_numpy(table).to(dev)
+    sl = torch.from_numpy(lens).to(dev)
+    cache = Q.Cache(k_pool, v_pool, meta, pt, sl)
+    Q.quest_build_meta(cache)
+    want_meta = O.build_meta(k_s, small_table, lens)
+    got_meta = meta[ids].view(torch.int16).cpu().numpy().view(np.float16)
+    assert np.array_equal(got_meta.view(np.uint16), want_meta.view(np.uint16))
+    scores = torch.zeros((1, H, table.shape[1]), dtype=torch.float32, device=dev)
+    qd = torch.from_numpy(q.view(np.int16)).to(dev).view(torch.float16)
+    Q.quest_estimate(cache, qd, scores)
+    idx = torch.zeros((1, H, 8), dtype=torch.int32, device=dev)
+    Q.quest_topk(cache, scores, 8, idx, None)
+    ws = torch.empty(max(Q.quest_workspace_bytes(cache, 8), 4) // 4, dtype=torch.float32, device=dev)
+    out = torch.zeros((1, H, D), dtype=torch.float32, device=dev)
+    Q.quest_sparse_decode(cache, qd, idx, 8, 1 / math.sqrt(D), out, None, ws)
+    torch.cuda.synchronize()
+    sc = O.estimate(want_meta, q, small_table, lens, S)
+    oidx, _ = O.topk(sc, lens, S, 8)
+    from gpu_util import check_selection
+    check_selection(idx.cpu().numpy(), sc, lens, S, 8)
+    want, _ = O.sparse_decode(k_s, v_s, q, small_table, lens, idx.cpu().numpy(), 1 / math.sqrt(D))
+    assert np.abs(out.cpu().numpy() - want).max() <= ATTN_TOL
