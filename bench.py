@@ -1,0 +1,289 @@
+#!/usr/bin/env python3
+"""Benchmark of the Quest decode hot path on one MI355X.
+
+A step is one layer-step of decode on the LongChat-7B-shaped workload
+(config 1: batch 1, 32 heads x 128, fp16 KV, 32k context, page 16, token
+budget 2048): append one token (KV write + min/max update), estimate page
+criticality, select the top 128 pages, sparse paged attention over them.
+Steps rotate over `--layers` distinct layer buffers, as the layers of a model
+do, so metadata and KV pages come from HBM rather than from the 256 MB
+last-level cache.  The K timed steps are captured once into a HIP graph and
+replayed, so host launch overhead is not what is measured.
+
+Prints ONE JSON line: value = microseconds per layer-step; next to it the
+achieved HBM GB/s on the bytes the method has to touch (metadata + selected KV
+pages, Section 3.5 of the paper), the library's own dense path (all pages) on
+the same buffers, the roofline entry of the dominant kernel and the CPU oracle
+timed on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--layers", type=int, default=16, help="distinct layer buffers to rotate over")
+    ap.add_argument("--config", type=int, default=1, help="workload id (1 = headline)")
+    ap.add_argument("--repeats", type=int, default=5, help="graph replays; the median is reported")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--eager", action="store_true", help="also time eager (per-call) launches")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (--gpus 1); the path shards over "
+              "heads/sequences without communication, see DESIGN.md", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2406_10774_amd import binding as Q, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    n_total = args.warmup + args.steps
+    n_layers = args.layers
+    visits = -(-n_total // n_layers)                      # appends per layer buffer
+    w = synth.workload(args.config, decode_steps=visits + 1)
+    B, H, S, D, K = w.batch, w.num_heads, w.page_size, w.head_dim, w.k_pages
+    scale = 1.0 / math.sqrt(D)
+
+    # ---------------------------------------------------------------- inputs
+    t0 = time.time()
+    table, N = synth.make_page_table(w, permute=False)
+    k_pool, v_pool, _ = synth.fill_pools(w, table, N, stale_fill=0.0, threads=16)
+    lens0 = np.array(w.seq_lens, np.int32)
+
+    def dev16(a):
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(dev).view(torch.float16)
+
+    k0, v0 = dev16(k_pool), dev16(v_pool)
+    pt = torch.from_numpy(table).to(dev)
+    # step i visits layer i % n_layers for the (i // n_layers + 1)-th time
+    lens_steps = np.stack([lens0 + (i // n_layers + 1) for i in range(n_total)]).astype(np.int32)
+    lens_dev = torch.from_numpy(lens_steps).to(dev)
+    lens0_dev = torch.from_numpy(lens0).to(dev)
+    q_all = dev16(np.stack([synth.gen_query(w, i) for i in range(n_total)]))
+    new_kv = [synth.gen_new_token(w, i) for i in range(n_total)]
+    kn_all = dev16(np.stack([k for k, _ in new_kv]))
+    vn_all = dev16(np.stack([v for _, v in new_kv]))
+
+    layers = []
+    for l in range(n_layers):
+        kp = k0 if l == 0 else k0.clone()
+        vp = v0 if l == 0 else v0.clone()
+        meta = torch.zeros((N, H, 2, D), dtype=torch.float16, device=dev)
+        Q.quest_build_meta(Q.Cache(kp, vp, meta, pt, lens0_dev))
+        layers.append((kp, vp, meta))
+    caches = [Q.Cache(*layers[i % n_layers], pt, lens_dev[i]) for i in range(n_total)]
+    scores = torch.zeros((B, H, table.shape[1]), dtype=torch.float32, device=dev)
+    idx = torch.zeros((B, H, K), dtype=torch.int32, device=dev)
+    out = torch.zeros((B, H, D), dtype=torch.float32, device=dev)
+    ws_bytes = max(Q.quest_workspace_bytes(caches[0], K), Q.quest_workspace_bytes(caches[0], 0), 4)
+    ws = torch.empty(ws_bytes // 4, dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+    gen_s = time.time() - t0
+
+    # ------------------------------------------------------------- the step
+    def sparse_step(i):
+        c = caches[i]
+        Q.quest_append_meta(c, kn_all[i], vn_all[i], True)
+        Q.quest_estimate(c, q_all[i], scores)
+        Q.quest_topk(c, scores, K, idx, None)
+        Q.quest_sparse_decode(c, q_all[i], idx, K, scale, out, None, ws)
+
+    def dense_step(i):
+        c = caches[i]
+        Q.quest_append_meta(c, kn_all[i], vn_all[i], True)
+        Q.quest_sparse_decode(c, q_all[i], None, 0, scale, out, None, ws)
+
+    def capture(fn, indices):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in indices:
+                fn(i)
+        return g
+
+    def time_graph(g, repeats):
+        """Median wall-clock seconds of one replay, synchronised on both sides."""
+        times = []
+        for _ in range(repeats):
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            g.replay()
+            torch.cuda.synchronize()
+            times.append(time.perf_counter() - t)
+        return float(np.median(times)), times
+
+    def time_graph_events(g, repeats):
+        """Median GPU seconds (HIP events on the launch stream) of one replay."""
+        times = []
+        for _ in range(repeats):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1) * 1e-3)
+        return float(np.median(times))
+
+    timed = list(range(args.warmup, n_total))
+    for i in range(args.warmup):                          # untimed warm-up, eager
+        sparse_step(i)
+    torch.cuda.synchronize()
+    g_sparse = capture(sparse_step, timed)
+    g_sparse.replay()
+    sec, all_sec = time_graph(g_sparse, args.repeats)
+    us_step = sec / args.steps * 1e6
+    us_step_events = time_graph_events(g_sparse, args.repeats) / args.steps * 1e6
+
+    g_dense = capture(dense_step, timed)
+    g_dense.replay()
+    dense_sec, _ = time_graph(g_dense, max(3, args.repeats // 2))
+    dense_us = dense_sec / args.steps * 1e6
+
+    eager_us = None
+    if args.eager:
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for i in timed:
+            sparse_step(i)
+        torch.cuda.synchronize()
+        eager_us = (time.perf_counter() - t) / args.steps * 1e6
+
+    # bytes the method has to move per step: metadata of every page + selected KV pages
+    pages_steps = [int(sum(-(-int(x) // S) for x in lens_steps[i])) for i in timed]
+    meta_bytes = float(np.mean([H * p * 512 for p in pages_steps]))
+    ksel = [sum(min(K, -(-int(x) // S)) for x in lens_steps[i]) for i in timed]
+    kv_bytes = float(np.mean([H * k * 8192 for k in ksel]))
+    dense_bytes = float(np.mean([H * p * 8192 for p in pages_steps]))
+    step_bytes = meta_bytes + kv_bytes
+    gbps = step_bytes / (us_step * 1e-6) / 1e9
+
+    # ------------------------------------------------ per-kernel launch times
+    def kernel_us(fn, reps=4):
+        g = capture(fn, timed * reps)
+        g.replay()
+        return time_graph_events(g, 3) / (len(timed) * reps) * 1e6
+
+    k_est = kernel_us(lambda i: Q.quest_estimate(caches[i], q_all[i], scores))
+    k_topk = kernel_us(lambda i: Q.quest_topk(caches[i], scores, K, idx, None))
+    k_dec = kernel_us(lambda i: Q.quest_sparse_decode(caches[i], q_all[i], idx, K, scale, out, None, ws))
+    k_app = kernel_us(lambda i: Q.quest_append_meta(caches[i], kn_all[i], vn_all[i], True))
+    k_dense = kernel_us(lambda i: Q.quest_sparse_decode(caches[i], q_all[i], None, 0, scale, out,
+                                                        None, ws), reps=1)
+    kernels = {
+        "append_meta_us": round(k_app, 3),
+        "estimate_us": round(k_est, 3), "estimate_gbps": round(meta_bytes / k_est / 1e3, 1),
+        "topk_us": round(k_topk, 3),
+        "sparse_decode_us": round(k_dec, 3), "sparse_decode_gbps": round(kv_bytes / k_dec / 1e3, 1),
+        "dense_decode_us": round(k_dense, 3), "dense_decode_gbps": round(dense_bytes / k_dense / 1e3, 1),
+    }
+    if k_est >= k_dec:
+        dom, dom_us, dom_bytes = "quest_estimate", k_est, meta_bytes
+    else:
+        dom, dom_us, dom_bytes = "quest_sparse_decode", k_dec, kv_bytes
+    achieved = dom_bytes / dom_us / 1e3
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                "traffic": load_traffic(dom)}
+
+    # ---------------------------------------------------------- CPU baseline
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(w, table, k_pool, v_pool, lens0, scale)
+
+    line = {
+        "metric": "sparse decode attn us/layer-step + achieved HBM GB/s (32 heads, 32k ctx, budget 2048)",
+        "value": round(us_step, 3), "unit": "us/layer-step",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(us_step * 1e-3, 6), "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16 in / f32 accumulate", "data": "synthetic",
+        "config": {"workload": w.name, "batch": B, "heads": H, "head_dim": D, "page_size": S,
+                   "context": int(lens0.max()), "token_budget": w.token_budget, "k_pages": K,
+                   "layer_buffers": n_layers, "launch": "hip-graph replay of the timed steps"},
+        "hbm_gbps": round(gbps, 1), "hbm_frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4),
+        "bytes_per_step": int(step_bytes), "us_per_step_gpu_events": round(us_step_events, 3),
+        "dense_us_per_step": round(dense_us, 3),
+        "dense_hbm_gbps": round(dense_bytes / (dense_us * 1e-6) / 1e9, 1),
+        "speedup_vs_own_dense": round(dense_us / us_step, 3),
+        "eager_us_per_step": None if eager_us is None else round(eager_us, 3),
+        "kernels": kernels, "roofline": roofline, "cpu_baseline": cpu,
+        "setup_s": round(gen_s, 1),
+    }
+    print(json.dumps(line))
+
+
+def load_traffic(kernel):
+    """HBM bytes per launch of `kernel` measured with rocprofv3 --pmc (FETCH_SIZE and
+    WRITE_SIZE runs, scaled by a copy kernel of known size); kept as a small text file
+    next to the profile summaries.  None if it has not been measured."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for ln in open(path):
+        parts = ln.split()
+        if len(parts) >= 2 and parts[0] == kernel:
+            return float(parts[1])
+    return None
+
+
+def cpu_baseline(w, table, k_pool, v_pool, lens0, scale):
+    """The oracle, as it stands, on the host: full layer-steps of the same workload."""
+    from oracle import quest_oracle as O
+    from paper_2406_10774_amd import synth
+    try:
+        from threadpoolctl import threadpool_limits
+    except ImportError:                                   # pragma: no cover
+        threadpool_limits = None
+    S = w.page_size
+    meta = O.build_meta(k_pool, table, lens0)
+    n = 3
+    cur = lens0.copy()
+
+    def run():
+        nonlocal meta, cur
+        t = time.perf_counter()
+        for i in range(n):
+            q = synth.gen_query(w, 1000 + i)
+            k_new, v_new = synth.gen_new_token(w, 1000 + i)
+            t_in = time.perf_counter()
+            cur = cur + 1
+            O.append_kv(k_pool, v_pool, k_new, v_new, table, cur)
+            meta = O.append_meta(meta, k_new, table, cur, S)
+            sc = O.estimate(meta, q, table, cur, S)
+            idx, _ = O.topk(sc, cur, S, w.k_pages)
+            O.sparse_decode(k_pool, v_pool, q, table, cur, idx, scale)
+            run.acc += time.perf_counter() - t_in
+        return time.perf_counter() - t
+    run.acc = 0.0
+    if threadpool_limits is not None:
+        with threadpool_limits(limits=1):
+            run()
+    else:
+        run()
+    return {"value": round(run.acc / n * 1e6, 1), "unit": "us/layer-step", "cores": 1,
+            "kind": "oracle", "sample": f"{n} full layer-steps of {w.name} (numpy float64, 1 thread)"}
+
+
+if __name__ == "__main__":
+    main()
