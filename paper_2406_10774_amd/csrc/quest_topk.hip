@@ -3,11 +3,21 @@
 //
 // Scores are mapped to unsigned 32-bit keys whose integer order equals the
 // order of the float values (-0 folded onto +0).  An MSB-first radix select
-// (four 8-bit digits, LDS histogram per digit) finds the key T of the K-th
-// largest score and how many keys equal to T still fit.  A final pass in page
-// order emits every page with key > T plus the first `need` pages with
-// key == T, each at the position given by a block-wide prefix count, so the
-// output is ascending and the lowest page index wins among equal scores.
+// (8-bit digits, LDS histogram per digit) narrows down the key of the K-th
+// largest score; it stops as soon as every key left in the threshold bin
+// belongs to the selection.  A final pass in page order emits every page above
+// the threshold bin plus the first `need` pages inside it, each at the position
+// given by a block-wide prefix count, so the output is ascending and the lowest
+// page index wins among equal scores.
+//
+// The kernel is latency-bound (a few thousand keys per head), so the work is
+// organised to shorten the dependent chain: keys live in registers (thread t
+// owns pages [t*ITEMS, (t+1)*ITEMS)), the score loads are issued before
+// seq_lens is known, a block-wide vote skips the first digit when all keys
+// share their top byte (scores of one head usually share sign and exponent),
+// every wave searches the histogram for the threshold bin itself so a pass
+// needs a single barrier, and same-digit lanes are combined into one LDS atomic
+// in the first pass executed, where nearly all keys hit the same few bins.
 #include "quest_common.h"
 
 namespace quest {
@@ -20,110 +30,218 @@ __device__ __forceinline__ uint32_t score_key(float s) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// Inclusive prefix sum over the 64 lanes: DPP row shifts inside each 16-lane
+// row, then the totals of the preceding rows.
 __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
-#pragma unroll
-  for (int d = 1; d < kWave; d <<= 1) {
-    const int o = __shfl_up(v, d);
-    if (lane >= d) v += o;
-  }
-  return v;
+  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);  // row_shr:1
+  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);  // row_shr:2
+  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);  // row_shr:4
+  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);  // row_shr:8
+  const int r0 = __builtin_amdgcn_readlane(v, 15);
+  const int r1 = __builtin_amdgcn_readlane(v, 31);
+  const int r2 = __builtin_amdgcn_readlane(v, 47);
+  const int row = lane >> 4;
+  return v + (row >= 1 ? r0 : 0) + (row >= 2 ? r1 : 0) + (row >= 3 ? r2 : 0);
 }
 
-// LDS: hist[256] | wave_gt[16] | wave_eq[16] | bcast[2] | keys[max_pages] (kLdsKeys only)
-constexpr int kTopkLdsHeaderWords = 256 + 16 + 16 + 2 + 6;  // padded to 296 words
+// Scan the 256-bin histogram from the top bin down for the bin that holds the
+// need-th largest key.  Lane l owns bins 255-4l .. 252-4l.  Every lane returns
+// the same (bin, keys above the bin, keys in the bin).
+struct BinHit {
+  int bin, above, count;
+};
+__device__ __forceinline__ BinHit find_bin(const uint32_t* hist, int need, int lane) {
+  const int top = 255 - 4 * lane;
+  const int c0 = hist[top], c1 = hist[top - 1], c2 = hist[top - 2], c3 = hist[top - 3];
+  const int tot = c0 + c1 + c2 + c3;
+  const int incl = wave_incl_scan(tot, lane);
+  int above = incl - tot;
+  const bool mine = above < need && need <= incl;
+  int bin = top, count = c0;
+  if (need > above + c0) {
+    above += c0, bin = top - 1, count = c1;
+    if (need > above + c1) {
+      above += c1, bin = top - 2, count = c2;
+      if (need > above + c2) above += c2, bin = top - 3, count = c3;
+    }
+  }
+  const int src = __ffsll((long long)__ballot(mine)) - 1;  // exactly one lane
+  BinHit r;
+  r.bin = __builtin_amdgcn_readlane(bin, src);
+  r.above = __builtin_amdgcn_readlane(above, src);
+  r.count = __builtin_amdgcn_readlane(count, src);
+  return r;
+}
 
-template <int kThreads, bool kLdsKeys>
+template <int kThreads, int kItems>
 __global__ __launch_bounds__(kThreads) void topk_kernel(
     const float* __restrict__ scores, const int32_t* __restrict__ seq_lens,
     int32_t* __restrict__ topk_idx, int32_t* __restrict__ k_eff, int num_heads, int max_pages,
     int k_pages) {
-  extern __shared__ uint32_t smem[];
-  uint32_t* hist = smem;
-  int* wave_gt = reinterpret_cast<int*>(smem + 256);
-  int* wave_eq = reinterpret_cast<int*>(smem + 272);
-  int* bcast = reinterpret_cast<int*>(smem + 288);
-  uint32_t* keys = smem + kTopkLdsHeaderWords;
+  constexpr int kWaves = kThreads / kWave;
+  __shared__ uint32_t hist[4][256];
+  __shared__ int wave_tot[kWaves];
+  __shared__ uint32_t vote;  // != 0: some key's top byte differs from page 0's
 
   const int h = blockIdx.x;
   const int b = blockIdx.y;
   const int tid = threadIdx.x;
   const int lane = lane_id();
   const int wave = tid >> 6;
-  constexpr int kWaves = kThreads / kWave;
-
-  const int num_pages = (seq_lens[b] + kPageSize - 1) / kPageSize;
-  const int K = min(k_pages, num_pages);
   const float* row = scores + ((size_t)b * num_heads + h) * max_pages;
   int32_t* out = topk_idx + ((size_t)b * num_heads + h) * k_pages;
-  if (h == 0 && tid == 0 && k_eff != nullptr) k_eff[b] = K;
 
+  // issue every load first: this thread's scores (entries past the valid pages
+  // are inside the row, so reading them is safe; they are masked below), the
+  // score of page 0 as the vote's reference, and the sequence length
+  const int base = tid * kItems;
+  float raw[kItems];
+#pragma unroll
+  for (int j = 0; j < kItems; ++j) raw[j] = base + j < max_pages ? row[base + j] : 0.f;
+  const float raw0 = row[0];
+  const int seq_len = seq_lens[b];
+
+  for (int i = tid; i < 4 * 256; i += kThreads) (&hist[0][0])[i] = 0;
+  if (tid == 0) vote = 0;
+  __syncthreads();
+
+  const int num_pages = (seq_len + kPageSize - 1) / kPageSize;
+  const int K = min(k_pages, num_pages);
+  if (h == 0 && tid == 0 && k_eff != nullptr) k_eff[b] = K;
   if (K == num_pages) {  // everything is selected: identity list, padded with -1
     for (int i = tid; i < k_pages; i += kThreads) out[i] = i < K ? i : -1;
     return;
   }
 
-  auto key_at = [&](int i) -> uint32_t { return kLdsKeys ? keys[i] : score_key(row[i]); };
-
-  if (kLdsKeys)
-    for (int i = tid; i < num_pages; i += kThreads) keys[i] = score_key(row[i]);
-  if (tid < 256) hist[tid] = 0;
+  uint32_t key[kItems];
+  bool valid[kItems];
+  const uint32_t ref_top = score_key(raw0) & 0xff000000u;
+  bool differs = false;
+#pragma unroll
+  for (int j = 0; j < kItems; ++j) {
+    key[j] = score_key(raw[j]);
+    valid[j] = base + j < num_pages;
+    differs |= valid[j] && (key[j] & 0xff000000u) != ref_top;
+  }
+  if (__ballot(differs) != 0 && lane == 0) vote = 1;
   __syncthreads();
+  const bool skip_first = vote == 0;
 
-  // ---- radix select: after the loop `prefix` is the K-th largest key and
-  // `need` (>= 1) the number of keys equal to it that belong to the selection
+  // ---- radix select.  Invariant: the selection is every key whose bits above
+  // `shift + 8` ... are greater than `prefix`'s, plus `need` of the keys that
+  // match `prefix` on the bits decided so far.
+  uint32_t prefix = skip_first ? ref_top : 0u;
+  int need = K;
+  int decided_shift = skip_first ? 24 : 32;  // bits [decided_shift, 32) of the threshold are known
+  bool first_pass = true;
+#pragma unroll
+  for (int pass = 0; pass < 4; ++pass) {
+    if (pass == 0 && skip_first) continue;
+    const int shift = 24 - 8 * pass;
+    const uint32_t high_mask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
+    uint32_t* hp = hist[pass];
+#pragma unroll
+    for (int j = 0; j < kItems; ++j) {
+      const bool act = valid[j] && (key[j] & high_mask) == prefix;
+      const uint32_t digit = (key[j] >> shift) & 255u;
+      if (first_pass) {
+        // most lanes carry the same digit here: one atomic for all of them
+        const uint32_t dd = act ? digit : 0xffffffffu;
+        const uint32_t d0 = __builtin_amdgcn_readfirstlane(dd);
+        const unsigned long long same = __ballot(dd == d0);
+        if (d0 != 0xffffffffu && lane == __ffsll((long long)same) - 1)
+          atomicAdd(&hp[d0], (uint32_t)__popcll(same));
+        if (act && dd != d0) atomicAdd(&hp[digit], 1u);
+      } else if (act) {
+        atomicAdd(&hp[digit], 1u);
+      }
+    }
+    first_pass = false;
+    __syncthreads();
+    const BinHit hit = find_bin(hp, need, lane);
+    prefix |= (uint32_t)hit.bin << shift;
+    need -= hit.above;
+    decided_shift = shift;
+    if (need == hit.count) break;  // the whole bin is selected: no need to split it further
+  }
+
+  // ---- emit in page order.  key > bin: selected; key in bin: the first `need`.
+  const uint32_t T = prefix >> decided_shift;  // decided_shift <= 24
+  int n_gt = 0, n_eq = 0;
+  bool gt[kItems], eq[kItems];
+#pragma unroll
+  for (int j = 0; j < kItems; ++j) {
+    const uint32_t kd = key[j] >> decided_shift;
+    gt[j] = valid[j] && kd > T;
+    eq[j] = valid[j] && kd == T;
+    n_gt += gt[j];
+    n_eq += eq[j];
+  }
+  const int packed = n_gt | (n_eq << 16);  // rows handled here have fewer than 2^16 pages
+  const int incl = wave_incl_scan(packed, lane);
+  if (lane == kWave - 1) wave_tot[wave] = incl;
+  __syncthreads();
+  int before = incl - packed;
+  for (int w = 0; w < kWaves; ++w)
+    if (w < wave) before += wave_tot[w];
+  int gt_before = (uint32_t)before & 0xffffu, eq_before = (uint32_t)before >> 16;
+#pragma unroll
+  for (int j = 0; j < kItems; ++j) {
+    const bool sel = gt[j] || (eq[j] && eq_before < need);
+    if (sel) out[gt_before + min(eq_before, need)] = base + j;
+    gt_before += gt[j];
+    eq_before += eq[j];
+  }
+}
+
+// Fallback for rows too long for register-resident keys: keys are re-read from
+// global memory (L2) in every pass; same algorithm without the shortcuts.
+constexpr int kBigThreads = 1024;
+__global__ __launch_bounds__(kBigThreads) void topk_big_kernel(
+    const float* __restrict__ scores, const int32_t* __restrict__ seq_lens,
+    int32_t* __restrict__ topk_idx, int32_t* __restrict__ k_eff, int num_heads, int max_pages,
+    int k_pages) {
+  constexpr int kWaves = kBigThreads / kWave;
+  __shared__ uint32_t hist[256];
+  __shared__ int wave_gt[kWaves], wave_eq[kWaves];
+  const int h = blockIdx.x;
+  const int b = blockIdx.y;
+  const int tid = threadIdx.x;
+  const int lane = lane_id();
+  const int wave = tid >> 6;
+  const int num_pages = (seq_lens[b] + kPageSize - 1) / kPageSize;
+  const int K = min(k_pages, num_pages);
+  const float* row = scores + ((size_t)b * num_heads + h) * max_pages;
+  int32_t* out = topk_idx + ((size_t)b * num_heads + h) * k_pages;
+  if (h == 0 && tid == 0 && k_eff != nullptr) k_eff[b] = K;
+  if (K == num_pages) {
+    for (int i = tid; i < k_pages; i += kBigThreads) out[i] = i < K ? i : -1;
+    return;
+  }
   uint32_t prefix = 0;
   int need = K;
-#pragma unroll
   for (int pass = 0; pass < 4; ++pass) {
     const int shift = 24 - 8 * pass;
     const uint32_t high_mask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
-    for (int i = tid; i < num_pages; i += kThreads) {
-      const uint32_t key = key_at(i);
+    if (tid < 256) hist[tid] = 0;
+    __syncthreads();
+    for (int i = tid; i < num_pages; i += kBigThreads) {
+      const uint32_t key = score_key(row[i]);
       if ((key & high_mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
     }
     __syncthreads();
-    if (wave == 0) {
-      // lane l owns bins 255-4l .. 252-4l (descending), scan from the top bin down
-      const int top = 255 - 4 * lane;
-      const int c0 = hist[top], c1 = hist[top - 1], c2 = hist[top - 2], c3 = hist[top - 3];
-      hist[top] = 0;
-      hist[top - 1] = 0;
-      hist[top - 2] = 0;
-      hist[top - 3] = 0;
-      const int tot = c0 + c1 + c2 + c3;
-      const int incl = wave_incl_scan(tot, lane);
-      const int excl = incl - tot;
-      if (excl < need && need <= incl) {
-        int bin = top, above = excl;
-        if (need > above + c0) {
-          above += c0;
-          bin = top - 1;
-          if (need > above + c1) {
-            above += c1;
-            bin = top - 2;
-            if (need > above + c2) {
-              above += c2;
-              bin = top - 3;
-            }
-          }
-        }
-        bcast[0] = bin;
-        bcast[1] = above;
-      }
-    }
+    const BinHit hit = find_bin(hist, need, lane);
+    prefix |= (uint32_t)hit.bin << shift;
+    need -= hit.above;
     __syncthreads();
-    prefix |= (uint32_t)bcast[0] << shift;
-    need -= bcast[1];
   }
   const uint32_t T = prefix;
-
-  // ---- emit in page order: thread t owns the contiguous chunk [t*items, (t+1)*items)
-  const int items = (num_pages + kThreads - 1) / kThreads;
+  const int items = (num_pages + kBigThreads - 1) / kBigThreads;
   const int begin = min(tid * items, num_pages);
   const int end = min(begin + items, num_pages);
   int n_gt = 0, n_eq = 0;
   for (int i = begin; i < end; ++i) {
-    const uint32_t key = key_at(i);
+    const uint32_t key = score_key(row[i]);
     n_gt += key > T;
     n_eq += key == T;
   }
@@ -142,7 +260,7 @@ __global__ __launch_bounds__(kThreads) void topk_kernel(
     }
   }
   for (int i = begin; i < end; ++i) {
-    const uint32_t key = key_at(i);
+    const uint32_t key = score_key(row[i]);
     if (key > T) {
       out[gt_before + min(eq_before, need)] = i;
       ++gt_before;
@@ -153,21 +271,12 @@ __global__ __launch_bounds__(kThreads) void topk_kernel(
   }
 }
 
-template <int kThreads, bool kLdsKeys>
+template <int kThreads, int kItems>
 int launch_one(const quest_cache& c, const float* scores, int k_pages, int32_t* topk_idx,
-               int32_t* k_eff, size_t lds_bytes, hipStream_t s) {
-  auto kern = topk_kernel<kThreads, kLdsKeys>;
-  if (lds_bytes > 64 * 1024) {
-    // opt in to a large dynamic LDS allocation (gfx950 has 160 KiB per CU)
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-    if (e != hipSuccess) {
-      (void)hipGetLastError();
-      return 1;  // caller falls back to keys re-read from global memory
-    }
-  }
-  hipLaunchKernelGGL(kern, dim3(c.num_heads, c.batch), dim3(kThreads), lds_bytes, s, scores,
-                     c.seq_lens, topk_idx, k_eff, c.num_heads, c.max_pages_per_seq, k_pages);
+               int32_t* k_eff, hipStream_t s) {
+  hipLaunchKernelGGL((topk_kernel<kThreads, kItems>), dim3(c.num_heads, c.batch), dim3(kThreads), 0,
+                     s, scores, c.seq_lens, topk_idx, k_eff, c.num_heads, c.max_pages_per_seq,
+                     k_pages);
   return check_launch("quest_topk");
 }
 
@@ -175,16 +284,31 @@ int launch_one(const quest_cache& c, const float* scores, int k_pages, int32_t* 
 
 int launch_topk(const quest_cache& c, const float* scores, int k_pages, int32_t* topk_idx,
                 int32_t* k_eff, hipStream_t s) {
-  const size_t header = kTopkLdsHeaderWords * sizeof(uint32_t);
-  const size_t with_keys = header + (size_t)c.max_pages_per_seq * sizeof(uint32_t);
-  constexpr size_t kLdsLimit = 160 * 1024;
-  if (c.max_pages_per_seq <= 4096)
-    return launch_one<256, true>(c, scores, k_pages, topk_idx, k_eff, with_keys, s);
-  if (with_keys <= kLdsLimit) {
-    int r = launch_one<1024, true>(c, scores, k_pages, topk_idx, k_eff, with_keys, s);
-    if (r <= 0) return r;
-  }
-  return launch_one<1024, false>(c, scores, k_pages, topk_idx, k_eff, header, s);
+  const int mp = c.max_pages_per_seq;
+#define QUEST_TOPK_CASE(T, I) \
+  if (mp <= (T) * (I)) return launch_one<T, I>(c, scores, k_pages, topk_idx, k_eff, s)
+  // up to 8192 pages: 512 threads, smallest ITEMS that covers the row
+  QUEST_TOPK_CASE(512, 1);
+  QUEST_TOPK_CASE(512, 2);
+  QUEST_TOPK_CASE(512, 3);
+  QUEST_TOPK_CASE(512, 4);
+  QUEST_TOPK_CASE(512, 5);
+  QUEST_TOPK_CASE(512, 6);
+  QUEST_TOPK_CASE(512, 8);
+  QUEST_TOPK_CASE(512, 10);
+  QUEST_TOPK_CASE(512, 12);
+  QUEST_TOPK_CASE(512, 16);
+  // up to 65536 pages (the packed prefix counts hold 16 bits each)
+  QUEST_TOPK_CASE(1024, 12);
+  QUEST_TOPK_CASE(1024, 17);
+  QUEST_TOPK_CASE(1024, 24);
+  QUEST_TOPK_CASE(1024, 33);
+  QUEST_TOPK_CASE(1024, 48);
+  if (mp < 65536) return launch_one<1024, 64>(c, scores, k_pages, topk_idx, k_eff, s);
+#undef QUEST_TOPK_CASE
+  hipLaunchKernelGGL(topk_big_kernel, dim3(c.num_heads, c.batch), dim3(kBigThreads), 0, s, scores,
+                     c.seq_lens, topk_idx, k_eff, c.num_heads, c.max_pages_per_seq, k_pages);
+  return check_launch("quest_topk");
 }
 
 }  // namespace quest
