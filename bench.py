@@ -98,7 +98,7 @@ def main():
     idx = torch.zeros((B, H, K), dtype=torch.int32, device=dev)
     out = torch.zeros((B, H, D), dtype=torch.float32, device=dev)
     ws_bytes = max(Q.quest_workspace_bytes(caches[0], K), Q.quest_workspace_bytes(caches[0], 0), 4)
-    ws = torch.empty(ws_bytes // 4, dtype=torch.float32, device=dev)
+    ws = torch.zeros(ws_bytes // 4, dtype=torch.float32, device=dev)
     torch.cuda.synchronize()
     gen_s = time.time() - t0
 

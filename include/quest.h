@@ -80,8 +80,13 @@ typedef struct quest_cache {
 
 /* Bytes of device workspace quest_sparse_decode needs for this cache and
  * k_pages (k_pages <= 0: the dense path over all pages).  Pure host function.
- * The workspace holds the split-K partial results (running max, denominator
- * and un-normalised accumulator of each split).  *out_bytes may be 0. */
+ * The workspace holds one arrival counter per (sequence, head) and the split-K
+ * partial results (running max, denominator and un-normalised accumulator of
+ * each split).  *out_bytes may be 0.
+ * A workspace must be zero-filled once, after it is allocated and before its
+ * first use (e.g. hipMemset); every call leaves the counters at zero again, so
+ * the same workspace serves later calls, sparse or dense, on the same cache
+ * shape.  Calls that share a workspace must not overlap in time. */
 int quest_workspace_bytes(const quest_cache* cache, int32_t k_pages, size_t* out_bytes);
 
 /* Metadata of every page that holds at least one token (Section 3.4:
@@ -127,7 +132,8 @@ int quest_topk(const quest_cache* cache, const float* scores, int32_t k_pages,
  * topk_idx rows are read up to min(k_pages, P_b) entries and stop at the first
  * negative id.  topk_idx == NULL selects every page: the dense baseline
  * (k_pages is then ignored).  fp16 inputs, fp32 dot products, fp32 online
- * softmax over splits of the page list, merged in a second pass.  out is fp32
+ * softmax over splits of the page list; the split that finishes last merges
+ * them.  out is fp32
  * if out_is_fp16 == 0, else fp16 (rounded once, from the fp32 result).
  * workspace: at least quest_workspace_bytes(cache, topk_idx ? k_pages : 0). */
 int quest_sparse_decode(const quest_cache* cache, const void* q, const int32_t* topk_idx,

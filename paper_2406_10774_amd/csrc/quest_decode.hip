@@ -3,7 +3,7 @@
 // over the tokens of the selected pages only.  With no page list it runs over
 // every page: the dense baseline the paper compares against (Section 3.1).
 //
-// Split-K flash-decoding.  Grid = (split, head, sequence); each work-group of
+// Split-K flash-decoding.  One work-group per (sequence, head, split); each work-group of
 // four waves owns a contiguous slice of the head's page list, its waves take
 // the slice's pages round-robin.  A wave streams one (page, head) block of
 // keys and one of values per step (4 KiB each = 4 wave-wide 16-byte loads
@@ -13,12 +13,14 @@
 // reduction inside the 16-lane DPP row; each DPP row keeps its own online
 // softmax state (running max, denominator, 8 accumulator channels per lane) in
 // fp32, in the log2 domain.  Rows, waves and finally splits are merged with the
-// usual (max, sum, accumulator) rescaling; the split merge is a second kernel.
+// usual (max, sum, accumulator) rescaling; the split that finishes last merges
+// the partial results of all splits of its head.
 //
 // Single-query attention is a matrix-vector product (about one flop per byte
 // read), far below the machine balance, so there is no MFMA here: the kernel is
 // bound by how fast HBM delivers the 8 KiB per selected (page, head).
 #include "quest_common.h"
+#include "quest_team.h"
 
 #include <cmath>
 #include <cstdlib>
@@ -44,8 +46,12 @@ struct DecodeArgs {
   float* part_ml;           // [B*H*splits][2]   running max (log2 domain), denominator
   void* out;
   float* lse;
-  int num_heads, max_pages, k_pages, splits, out_is_fp16;
-  float scale_log2;  // sm_scale * log2(e)
+  uint64_t* counters;       // [B*H] team words (see quest_team.h); zero between launches
+  int batch, num_heads, max_pages, k_pages, splits, out_is_fp16;
+  int list_len;             // entries of the page list the splits divide: k_pages, or max_pages
+  int per_split;            // ceil(list_len / splits)
+  int force_device_fences;  // debug: take the cross-die exchange path
+  float scale_log2;         // sm_scale * log2(e)
 };
 
 struct PageRegs {
@@ -130,28 +136,46 @@ __device__ __forceinline__ void store_out(void* out, int out_is_fp16, size_t idx
     reinterpret_cast<float*>(out)[idx] = v;
 }
 
+// Grid is one-dimensional and die-aware: work-groups whose ids are equal modulo
+// 8 run on the same die (round-robin placement), and
+// all splits of one (sequence, head) are given ids with the same i % 8, so
+// their partial results meet in one L2 and the last split to finish can merge
+// them without a second launch and without device-wide cache maintenance.
+// The placement is verified at run time (see quest_team.h): if the splits of a
+// head do not all run on one die, the exchange falls back to device-scope
+// release/acquire fences: slow, still correct.
 __global__ __launch_bounds__(kDecThreads) void decode_split_kernel(const DecodeArgs a) {
   __shared__ float sm_acc[kDecWaves][kHeadDim];
   __shared__ float sm_m[kDecWaves], sm_l[kDecWaves];
+  __shared__ uint32_t sm_before[2];
 
-  const int split = blockIdx.x;
-  const int h = blockIdx.y;
-  const int b = blockIdx.z;
+  const int slot = blockIdx.x & 7;
+  const int rank = blockIdx.x >> 3;
+  const int split = rank % a.splits;
+  const int bh_i = (rank / a.splits) * 8 + slot;
+  if (bh_i >= a.batch * a.num_heads) return;
+  const int b = bh_i / a.num_heads;
+  const int h = bh_i - b * a.num_heads;
+  const size_t bh = bh_i;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = lane_id();
   const int grp = lane >> 4;
   const int c = lane & 15;
-  const size_t bh = (size_t)b * a.num_heads + h;
+  const uint32_t die = xcc_id();
+  uint64_t* team_word = a.counters + bh * kTeamWordStride;
+  if (a.splits > 1 && threadIdx.x == 0) team_checkin(team_word, die);
 
-  const int seq_len = a.seq_lens[b];
-  const int num_pages = (seq_len + kPageSize - 1) / kPageSize;
-  const int n_sel = a.topk_idx ? min(a.k_pages, num_pages) : num_pages;
-  const int per_split = (n_sel + a.splits - 1) / a.splits;
-  const int begin = split * per_split;
-  const int end = min(n_sel, begin + per_split);
+  // This wave's share of the page list: positions begin + wave + 4 i.  The list
+  // length used for the split (k_pages, or max_pages without a list) is known
+  // on the host, so list entries and page-table entries are fetched without
+  // waiting for seq_lens; entries past the valid pages are dropped afterwards.
+  const int begin = split * a.per_split;
+  const int end = min(a.list_len, begin + a.per_split);
+  const int iters = (a.per_split + kDecWaves - 1) / kDecWaves;
   const int32_t* idx_row = a.topk_idx ? a.topk_idx + bh * a.k_pages : nullptr;
   const int32_t* pt = a.page_table + (size_t)b * a.max_pages;
 
+  const int seq_len = a.seq_lens[b];
   const uint4 qv = ld16(a.q + bh * (kHeadDim * 2) + c * 16);
 
   Softmax st;
@@ -160,25 +184,33 @@ __global__ __launch_bounds__(kDecThreads) void decode_split_kernel(const DecodeA
 #pragma unroll
   for (int j = 0; j < 8; ++j) st.acc[j] = 0.f;
 
-  // logical page at list position pos, or -1 past the end of this wave's share
-  auto page_at = [&](int pos) -> int {
-    if (pos >= end) return -1;
-    return idx_row ? idx_row[pos] : pos;
-  };
+  for (int chunk = 0; chunk < iters; chunk += kWave) {
+    // lane i holds list entry chunk + i of this wave: logical page and physical page
+    const int pos = begin + wave + kDecWaves * (chunk + lane);
+    int lp_v = -1;
+    if (chunk + lane < iters && pos < end) lp_v = idx_row ? idx_row[pos] : pos;
+    int ph_v = 0;
+    if (lp_v >= 0 && lp_v < a.max_pages) ph_v = pt[lp_v];
+    const int num_pages = (seq_len + kPageSize - 1) / kPageSize;
+    if (lp_v >= num_pages) lp_v = -1;
+    const int n_here = min(kWave, iters - chunk);
 
-  PageRegs ra, rb;
-  int pos = begin + wave;
-  int lp = page_at(pos);
-  if (lp >= 0) load_page(ra, a, h, seq_len, lp, pt[lp], lane);
-  while (lp >= 0) {
-    int lp_b = page_at(pos + kDecWaves);
-    if (lp_b >= 0) load_page(rb, a, h, seq_len, lp_b, pt[lp_b], lane);
-    fold_page(st, ra, qv, a.scale_log2, grp);
-    if (lp_b < 0) break;
-    pos += 2 * kDecWaves;
-    lp = page_at(pos);
-    if (lp >= 0) load_page(ra, a, h, seq_len, lp, pt[lp], lane);
-    fold_page(st, rb, qv, a.scale_log2, grp);
+    PageRegs ra, rb;
+    int j = 0;
+    int lp = __builtin_amdgcn_readlane(lp_v, 0);
+    if (lp >= 0) load_page(ra, a, h, seq_len, lp, __builtin_amdgcn_readlane(ph_v, 0), lane);
+    while (lp >= 0) {
+      int lp_b = -1;
+      if (j + 1 < n_here) lp_b = __builtin_amdgcn_readlane(lp_v, j + 1);
+      if (lp_b >= 0) load_page(rb, a, h, seq_len, lp_b, __builtin_amdgcn_readlane(ph_v, j + 1), lane);
+      fold_page(st, ra, qv, a.scale_log2, grp);
+      if (lp_b < 0) break;
+      j += 2;
+      lp = -1;
+      if (j < n_here) lp = __builtin_amdgcn_readlane(lp_v, j);
+      if (lp >= 0) load_page(ra, a, h, seq_len, lp, __builtin_amdgcn_readlane(ph_v, j), lane);
+      fold_page(st, rb, qv, a.scale_log2, grp);
+    }
   }
 
   // the four DPP rows of the wave, then the four waves of the group
@@ -194,49 +226,75 @@ __global__ __launch_bounds__(kDecThreads) void decode_split_kernel(const DecodeA
   }
   __syncthreads();
   const int t = threadIdx.x;
-  if (t < kHeadDim) {
-    float m_tot = sm_m[0];
+  float m_tot = sm_m[0];
 #pragma unroll
-    for (int w = 1; w < kDecWaves; ++w) m_tot = fmaxf(m_tot, sm_m[w]);
-    float l_tot = 0.f, acc = 0.f;
+  for (int w = 1; w < kDecWaves; ++w) m_tot = fmaxf(m_tot, sm_m[w]);
+  float l_tot = 0.f, acc = 0.f;
 #pragma unroll
-    for (int w = 0; w < kDecWaves; ++w) {
-      const float f = __builtin_amdgcn_exp2f(sm_m[w] - m_tot);
-      l_tot += sm_l[w] * f;
-      acc += sm_acc[w][t] * f;
-    }
-    if (a.splits == 1) {
+  for (int w = 0; w < kDecWaves; ++w) {
+    const float f = __builtin_amdgcn_exp2f(sm_m[w] - m_tot);
+    l_tot += sm_l[w] * f;
+    acc += sm_acc[w][t & (kHeadDim - 1)] * f;
+  }
+  if (a.splits == 1) {
+    if (t < kHeadDim) {
       store_out(a.out, a.out_is_fp16, bh * kHeadDim + t, acc / l_tot);
       if (t == 0 && a.lse) a.lse[bh] = (m_tot + __builtin_amdgcn_logf(l_tot)) * kLn2;
-    } else {
-      const size_t ps = bh * a.splits + split;
-      a.part_acc[ps * kHeadDim + t] = acc;
-      if (t == 0) {
-        a.part_ml[ps * 2 + 0] = m_tot;
-        a.part_ml[ps * 2 + 1] = l_tot;
-      }
     }
+    return;
   }
-}
 
-// Second pass: one work-group per (sequence, head), thread t = output channel.
-__global__ __launch_bounds__(kHeadDim) void decode_merge_kernel(const DecodeArgs a) {
-  const int h = blockIdx.x;
-  const int b = blockIdx.y;
-  const int t = threadIdx.x;
-  const size_t bh = (size_t)b * a.num_heads + h;
-  const float* ml = a.part_ml + bh * a.splits * 2;
-  const float* pacc = a.part_acc + bh * a.splits * kHeadDim;
-  float m_tot = kNegBig;
-  for (int s = 0; s < a.splits; ++s) m_tot = fmaxf(m_tot, ml[2 * s]);
-  float l_tot = 0.f, acc = 0.f;
-  for (int s = 0; s < a.splits; ++s) {
-    const float f = __builtin_amdgcn_exp2f(ml[2 * s] - m_tot);
-    l_tot += ml[2 * s + 1] * f;
-    acc += pacc[(size_t)s * kHeadDim + t] * f;
+  // ---- publish this split's partial; the split that finishes last merges
+  const size_t ps = bh * a.splits + split;
+  if (t < kHeadDim) a.part_acc[ps * kHeadDim + t] = acc;
+  if (t == 0) {
+    a.part_ml[ps * 2 + 0] = m_tot;
+    a.part_ml[ps * 2 + 1] = l_tot;
   }
-  store_out(a.out, a.out_is_fp16, bh * kHeadDim + t, acc / l_tot);
-  if (t == 0 && a.lse) a.lse[bh] = (m_tot + __builtin_amdgcn_logf(l_tot)) * kLn2;
+  wait_stores();
+  __syncthreads();
+  if (t == 0) {
+    const uint64_t before = team_publish(team_word, a.splits, die, a.force_device_fences);
+    sm_before[0] = (uint32_t)before;
+    sm_before[1] = (uint32_t)(before >> 32);
+  }
+  __syncthreads();
+  const uint64_t before = sm_before[0] | ((uint64_t)sm_before[1] << 32);
+  if (!team_is_last(before, a.splits)) return;
+  team_acquire(before, a.splits, die, a.force_device_fences);
+  if (t == 0) team_reset(team_word);
+
+  // one pass over the splits in chunks of 16, all loads of a chunk in flight at
+  // once, with a running maximum (the same rescaling as between pages)
+  if (t >= kHeadDim) return;
+  const float* ml = a.part_ml + bh * a.splits * 2;
+  const float* pacc = a.part_acc + bh * a.splits * kHeadDim + t;
+  float mx = kNegBig, l_all = 0.f, o = 0.f;
+  for (int s0 = 0; s0 < a.splits; s0 += 16) {
+    float pm[16], pl[16], pa[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int sidx = min(s0 + i, a.splits - 1);
+      pm[i] = team_ld(ml + 2 * sidx);
+      pl[i] = team_ld(ml + 2 * sidx + 1);
+      pa[i] = team_ld(pacc + (size_t)sidx * kHeadDim);
+    }
+    float cm = mx;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) cm = fmaxf(cm, pm[i]);
+    const float rescale = __builtin_amdgcn_exp2f(mx - cm);
+    l_all *= rescale;
+    o *= rescale;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float f = s0 + i < a.splits ? __builtin_amdgcn_exp2f(pm[i] - cm) : 0.f;
+      l_all += pl[i] * f;
+      o += pa[i] * f;
+    }
+    mx = cm;
+  }
+  store_out(a.out, a.out_is_fp16, bh * kHeadDim + t, o / l_all);
+  if (t == 0 && a.lse) a.lse[bh] = (mx + __builtin_amdgcn_logf(l_all)) * kLn2;
 }
 
 int env_int(const char* name, int fallback) {
@@ -246,31 +304,50 @@ int env_int(const char* name, int fallback) {
 
 }  // namespace
 
-// Number of splits of a head's page list.  Sized so that a split holds about
-// eight pages (two per wave: both in flight at once) while the whole launch
-// stays within a few thousand work-groups.
-int decode_num_splits(const quest_cache& c, int k_pages) {
-  static const int pages_per_split = env_int("QUEST_DECODE_PAGES_PER_SPLIT", 8);
-  static const int max_groups = env_int("QUEST_DECODE_MAX_GROUPS", 8192);
-  const int n_sel = k_pages > 0 ? (k_pages < c.max_pages_per_seq ? k_pages : c.max_pages_per_seq)
-                                : c.max_pages_per_seq;
+// Number of splits of a head's page list.  A split holds at least sixteen pages
+// (four per wave, two in flight at a time), and the whole launch stays within
+// the ~1000 work-groups that are resident at once, so that all splits of a head
+// start together (the condition for the cheap same-die exchange) and the
+// merge reads few partial results.  Both knobs can be overridden through the
+// environment for tuning sweeps.
+namespace {
+struct SplitPlan {
+  int list_len, per_split, splits;
+};
+SplitPlan plan_splits(const quest_cache& c, int k_pages) {
+  static const int pages_per_split = env_int("QUEST_DECODE_PAGES_PER_SPLIT", 16);
+  static const int max_groups = env_int("QUEST_DECODE_MAX_GROUPS", 1024);
+  SplitPlan p;
+  p.list_len = k_pages > 0 ? (k_pages < c.max_pages_per_seq ? k_pages : c.max_pages_per_seq)
+                           : c.max_pages_per_seq;
   const long bh = (long)c.batch * c.num_heads;
-  long splits = (n_sel + pages_per_split - 1) / pages_per_split;
+  long splits = (p.list_len + pages_per_split - 1) / pages_per_split;
   const long cap = max_groups / bh > 0 ? max_groups / bh : 1;
   if (splits > cap) splits = cap;
   if (splits < 1) splits = 1;
-  return (int)splits;
+  if (splits > kMaxTeamSize) splits = kMaxTeamSize;
+  p.per_split = (int)((p.list_len + splits - 1) / splits);
+  p.splits = (p.list_len + p.per_split - 1) / p.per_split;  // no empty split
+  return p;
 }
+// One team word per (sequence, head), each in a 256-byte slot of its own.
+size_t counter_bytes(const quest_cache& c) {
+  return (size_t)c.batch * c.num_heads * kTeamWordStride * sizeof(uint64_t);
+}
+}  // namespace
+
+int decode_num_splits(const quest_cache& c, int k_pages) { return plan_splits(c, k_pages).splits; }
 
 size_t decode_workspace_bytes(const quest_cache& c, int k_pages) {
-  const size_t splits = decode_num_splits(c, k_pages);
+  const size_t splits = plan_splits(c, k_pages).splits;
   if (splits == 1) return 0;
-  return (size_t)c.batch * c.num_heads * splits * (kHeadDim + 2) * sizeof(float);
+  return counter_bytes(c) + (size_t)c.batch * c.num_heads * splits * (kHeadDim + 2) * sizeof(float);
 }
 
 int launch_sparse_decode(const quest_cache& c, const void* q, const int32_t* topk_idx, int k_pages,
                          float sm_scale, void* out, int out_is_fp16, float* lse, void* workspace,
                          hipStream_t s) {
+  static const int force_fences = env_int("QUEST_FORCE_DEVICE_FENCES", 0);
   DecodeArgs a;
   a.k_pool = (const char*)c.k_pool;
   a.v_pool = (const char*)c.v_pool;
@@ -278,23 +355,27 @@ int launch_sparse_decode(const quest_cache& c, const void* q, const int32_t* top
   a.page_table = c.page_table;
   a.seq_lens = c.seq_lens;
   a.topk_idx = topk_idx;
+  a.batch = c.batch;
   a.num_heads = c.num_heads;
   a.max_pages = c.max_pages_per_seq;
   a.k_pages = topk_idx ? k_pages : 0;
-  a.splits = decode_num_splits(c, a.k_pages);
+  const SplitPlan p = plan_splits(c, a.k_pages);
+  a.splits = p.splits;
+  a.list_len = p.list_len;
+  a.per_split = p.per_split;
+  a.force_device_fences = force_fences;
   a.out = out;
   a.out_is_fp16 = out_is_fp16;
   a.lse = lse;
   a.scale_log2 = sm_scale * kLog2e;
   const size_t n_part = (size_t)c.batch * c.num_heads * a.splits;
-  a.part_acc = (float*)workspace;
+  a.counters = (uint64_t*)workspace;
+  a.part_acc = workspace ? (float*)((char*)workspace + counter_bytes(c)) : nullptr;
   a.part_ml = a.part_acc ? a.part_acc + n_part * kHeadDim : nullptr;
-  hipLaunchKernelGGL(decode_split_kernel, dim3(a.splits, c.num_heads, c.batch), dim3(kDecThreads), 0,
-                     s, a);
-  int r = check_launch("quest_sparse_decode (split pass)");
-  if (r != QUEST_OK || a.splits == 1) return r;
-  hipLaunchKernelGGL(decode_merge_kernel, dim3(c.num_heads, c.batch), dim3(kHeadDim), 0, s, a);
-  return check_launch("quest_sparse_decode (merge pass)");
+  const long bh8 = ((long)c.batch * c.num_heads + 7) / 8;
+  hipLaunchKernelGGL(decode_split_kernel, dim3((unsigned)(bh8 * 8 * a.splits)), dim3(kDecThreads), 0, s,
+                     a);
+  return check_launch("quest_sparse_decode");
 }
 
 }  // namespace quest

@@ -68,7 +68,7 @@ class Layer:
         if topk_idx is not None:
             idx = torch.from_numpy(np.ascontiguousarray(topk_idx, dtype=np.int32)).to(self.dev)
         ws_bytes = Q.quest_workspace_bytes(self.cache, k_pages if idx is not None else 0)
-        ws = torch.empty(max(ws_bytes, 4) // 4, dtype=torch.float32, device=self.dev)
+        ws = torch.zeros(max(ws_bytes, 4) // 4, dtype=torch.float32, device=self.dev)
         out = torch.full((self.B, self.H, self.D), float("nan"),
                          dtype=torch.float16 if fp16_out else torch.float32, device=self.dev)
         lse = torch.full((self.B, self.H), float("nan"), dtype=torch.float32, device=self.dev) \

@@ -40,8 +40,9 @@ def test_workspace_bytes_is_pure_and_consistent():
     sparse = out.value
     assert lib.quest_workspace_bytes(ctypes.byref(c), 0, ctypes.byref(out)) == 0
     dense = out.value
-    # partials: (D + 2) floats per (head, split); dense path uses at least as many splits
-    assert sparse % (32 * 130 * 4) == 0 and dense % (32 * 130 * 4) == 0
+    # one 256-byte counter slot per head + (D + 2) floats per (head, split);
+    # the dense path uses at least as many splits
+    assert (sparse - 32 * 256) % (32 * 130 * 4) == 0 and (dense - 32 * 256) % (32 * 130 * 4) == 0
     assert dense >= sparse > 0
     assert lib.quest_workspace_bytes(ctypes.byref(c), 128, None) == -1
 

@@ -248,7 +248,7 @@ def test_offsets_beyond_4gib():
     Q.quest_estimate(cache, qd, scores)
     idx = torch.zeros((1, H, 8), dtype=torch.int32, device=dev)
     Q.quest_topk(cache, scores, 8, idx, None)
-    ws = torch.empty(max(Q.quest_workspace_bytes(cache, 8), 4) // 4, dtype=torch.float32, device=dev)
+    ws = torch.zeros(max(Q.quest_workspace_bytes(cache, 8), 4) // 4, dtype=torch.float32, device=dev)
     out = torch.zeros((1, H, D), dtype=torch.float32, device=dev)
     Q.quest_sparse_decode(cache, qd, idx, 8, 1 / math.sqrt(D), out, None, ws)
     torch.cuda.synchronize()
