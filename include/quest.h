@@ -11,6 +11,7 @@
  *     after prefill :  quest_build_meta
  *     every token   :  quest_append_meta -> quest_estimate -> quest_topk
  *                      -> quest_sparse_decode
+ *                      (quest_append_estimate fuses the first two launches)
  *
  * Conventions for every entry point
  *   - All data pointers are DEVICE pointers owned by the caller.  The library
@@ -115,6 +116,14 @@ int quest_append_meta(const quest_cache* cache, const void* k_new, const void* v
  * unscaled; fp16 products are exact in fp32, accumulation is fp32.  Entries
  * p >= ceil(seq_lens[b]/S) of a row are not written. */
 int quest_estimate(const quest_cache* cache, const void* q, float* scores, void* stream);
+
+/* quest_append_meta followed by quest_estimate in one launch (both halves of
+ * Algorithm 1 for the step's new token and new query): same arguments, same
+ * results in k_pool / v_pool / meta / scores, bit for bit.  The wave that scores
+ * the newest token's page performs the insertion on the metadata it holds in
+ * registers. */
+int quest_append_estimate(const quest_cache* cache, const void* k_new, const void* v_new,
+                          int32_t k_pool_write, const void* q, float* scores, void* stream);
 
 /* Top-K filtering (Section 3.4): for every (b, h) the K_b = min(k_pages, P_b)
  * pages with the largest score among the P_b = ceil(seq_lens[b]/S) valid ones.

@@ -18,7 +18,7 @@ STATUS_NAMES = {0: "QUEST_OK", -1: "QUEST_ERR_NULL", -2: "QUEST_ERR_SHAPE",
                 -3: "QUEST_ERR_UNSUPPORTED", -4: "QUEST_ERR_WORKSPACE", -5: "QUEST_ERR_HIP"}
 
 EXPORTS = ("quest_workspace_bytes", "quest_build_meta", "quest_append_meta", "quest_estimate",
-           "quest_topk", "quest_sparse_decode", "quest_last_error")
+           "quest_append_estimate", "quest_topk", "quest_sparse_decode", "quest_last_error")
 
 
 class QuestError(RuntimeError):
@@ -57,6 +57,7 @@ def load():
     lib.quest_build_meta.argtypes = [cp, vp]
     lib.quest_append_meta.argtypes = [cp, vp, vp, i32, vp]
     lib.quest_estimate.argtypes = [cp, vp, vp, vp]
+    lib.quest_append_estimate.argtypes = [cp, vp, vp, i32, vp, vp, vp]
     lib.quest_topk.argtypes = [cp, vp, i32, vp, vp, vp]
     lib.quest_sparse_decode.argtypes = [cp, vp, vp, i32, f32, vp, i32, vp, vp, ctypes.c_size_t, vp]
     for name in EXPORTS[:-1]:
@@ -120,6 +121,12 @@ def quest_append_meta(cache: Cache, k_new, v_new=None, k_pool_write=False, strea
 
 def quest_estimate(cache: Cache, q, scores, stream=None):
     _check(load().quest_estimate(cache.ref, _ptr(q), _ptr(scores), _stream(stream)))
+
+
+def quest_append_estimate(cache: Cache, k_new, v_new, k_pool_write, q, scores, stream=None):
+    _check(load().quest_append_estimate(cache.ref, _ptr(k_new), _ptr(v_new),
+                                        int(bool(k_pool_write)), _ptr(q), _ptr(scores),
+                                        _stream(stream)))
 
 
 def quest_topk(cache: Cache, scores, k_pages, topk_idx, k_eff=None, stream=None):

@@ -111,6 +111,23 @@ int quest_estimate(const quest_cache* cache, const void* q, float* scores, void*
   return launch_estimate(*cache, q, scores, (hipStream_t)stream);
 }
 
+int quest_append_estimate(const quest_cache* cache, const void* k_new, const void* v_new,
+                          int32_t k_pool_write, const void* q, float* scores, void* stream) {
+  int r = check_cache(cache, "quest_append_estimate");
+  if (r != QUEST_OK) return r;
+  if (cache->meta == nullptr || k_new == nullptr || q == nullptr || scores == nullptr) {
+    set_error("quest_append_estimate: meta, k_new, q and scores must not be NULL");
+    return QUEST_ERR_NULL;
+  }
+  if (k_pool_write &&
+      (v_new == nullptr || cache->k_pool == nullptr || cache->v_pool == nullptr)) {
+    set_error("quest_append_estimate: k_pool_write needs v_new, k_pool and v_pool");
+    return QUEST_ERR_NULL;
+  }
+  return launch_append_estimate(*cache, k_new, v_new, k_pool_write != 0, q, scores,
+                                (hipStream_t)stream);
+}
+
 int quest_topk(const quest_cache* cache, const float* scores, int32_t k_pages, int32_t* topk_idx,
                int32_t* k_eff, void* stream) {
   int r = check_cache(cache, "quest_topk");

@@ -31,6 +31,8 @@ int launch_build_meta(const quest_cache& c, hipStream_t s);
 int launch_append_meta(const quest_cache& c, const void* k_new, const void* v_new,
                        int k_pool_write, hipStream_t s);
 int launch_estimate(const quest_cache& c, const void* q, float* scores, hipStream_t s);
+int launch_append_estimate(const quest_cache& c, const void* k_new, const void* v_new,
+                           int k_pool_write, const void* q, float* scores, hipStream_t s);
 int launch_topk(const quest_cache& c, const float* scores, int k_pages, int32_t* topk_idx,
                 int32_t* k_eff, hipStream_t s);
 int decode_num_splits(const quest_cache& c, int k_pages);

@@ -47,6 +47,11 @@ class Layer:
         Q.quest_append_meta(self.cache, self.half(k_new), None if v_new is None else self.half(v_new),
                             write)
 
+    def append_estimate(self, k_new, v_new, q, write=True):
+        Q.quest_append_estimate(self.cache, self.half(k_new), self.half(v_new), write, self.half(q),
+                                self.scores)
+        return self.scores.cpu().numpy()
+
     def estimate(self, q):
         Q.quest_estimate(self.cache, self.half(q), self.scores)
         return self.scores.cpu().numpy()

@@ -15,6 +15,10 @@ pytestmark = pytest.mark.gpu
 ATTN_TOL = 2e-3
 
 
+def torch_index(layer, ids):
+    return layer.torch.from_numpy(np.asarray(ids, np.int64)).to(layer.dev)
+
+
 def run_chain(w, steps, permute):
     from gpu_util import Layer, check_selection, score_tolerance
     S, D = w.page_size, w.head_dim
@@ -33,15 +37,20 @@ def run_chain(w, steps, permute):
     near_ties = 0
     for step in range(steps):
         q = synth.gen_query(w, step)
+        fused = step % 2 == 1                          # odd steps: one launch for append + estimate
         if step > 0:                                   # append one token, then attend
             k_new, v_new = synth.gen_new_token(w, step)
             cur += 1
             layer.set_seq_lens(cur)
-            layer.append(k_new, v_new, write=True)
+            if fused:
+                got_sc = layer.append_estimate(k_new, v_new, q)
+            else:
+                layer.append(k_new, v_new, write=True)
             O.append_kv(k_pool, v_pool, k_new, v_new, table, cur)
             meta = O.append_meta(meta, k_new, table, cur, S)
         sc = O.estimate(meta, q, table, cur, S)
-        got_sc = layer.estimate(q)
+        if not (fused and step > 0):
+            got_sc = layer.estimate(q)
         tol = score_tolerance(meta, q, table, cur, S)
         for b in range(w.batch):
             P = -(-int(cur[b]) // S)
@@ -53,10 +62,19 @@ def run_chain(w, steps, permute):
         got, lse = layer.decode(q, got_idx, w.k_pages)
         assert np.abs(got - want).max() <= ATTN_TOL, step
         assert np.abs(lse - want_lse).max() <= ATTN_TOL, step
-    # metadata maintained over the steps == oracle's == rebuilt
+    # metadata and pools maintained over the steps == oracle's
     got_meta = layer.np16(layer.meta)
     mapped = np.unique(np.concatenate([table[b, :-(-int(cur[b]) // S)] for b in range(w.batch)]))
     assert np.array_equal(got_meta[mapped].view(np.uint16), meta[mapped].view(np.uint16))
+    last = np.array([table[b, (int(cur[b]) - 1) // S] for b in range(w.batch)])
+    n_last = [(int(cur[b]) - 1) % S + 1 for b in range(w.batch)]
+    got_k, got_v = layer.np16(layer.k_pool[torch_index(layer, last)]), \
+        layer.np16(layer.v_pool[torch_index(layer, last)])
+    for i, b in enumerate(range(w.batch)):             # the appended tokens landed in their slots
+        assert np.array_equal(got_k[i, :, :n_last[b]].view(np.uint16),
+                              k_pool[last[b], :, :n_last[b]].view(np.uint16))
+        assert np.array_equal(got_v[i, :, :n_last[b]].view(np.uint16),
+                              v_pool[last[b], :, :n_last[b]].view(np.uint16))
     # dense path on the same buffers
     q = synth.gen_query(w, 0)
     want, want_lse = O.sparse_decode(k_pool, v_pool, q, table, cur, None, scale)

@@ -135,6 +135,41 @@ def test_topk_exact_on_shared_scores(ragged, k_pages):
     assert np.array_equal(got, want)
 
 
+@pytest.mark.parametrize("max_pages,lens", [
+    (4096, (16 * 4096, 16 * 3000 + 1)),        # 512 threads x 8 keys
+    (8192, (16 * 8192, 16 * 5000)),            # 512 x 16
+    (12288, (16 * 12288 - 3, 16 * 9000)),      # 1024 x 12
+    (32769, (16 * 32769, 16 * 20000 + 9)),     # 1024 x 33
+    (65535, (16 * 65535, 16 * 40000)),         # 1024 x 64
+    (70000, (16 * 70000, 16 * 66000)),         # rows too long for registers: keys re-read from memory
+])
+def test_topk_long_rows(max_pages, lens):
+    """Every register-tiling variant of the selection kernel, scores only."""
+    import torch
+    from paper_2406_10774_amd import binding as Q
+    B, H, S = 2, 3, 16
+    dev = "cuda:0"
+    rng = np.random.default_rng(max_pages)
+    sc = (rng.standard_normal((B, H, max_pages)) * 30 + 200).astype(np.float32)
+    sc[0, 1] = np.round(sc[0, 1])                      # ties
+    sc[1, 2] = 7.0                                     # all equal
+    sc[1, 0, ::3] *= -1                                # mixed signs: no common top byte
+    lens = np.array(lens, np.int32)
+    # placeholder pools: the selection kernel never touches them
+    dummy = torch.zeros((1, H, S, 128), dtype=torch.float16, device=dev)
+    meta = torch.zeros((1, H, 2, 128), dtype=torch.float16, device=dev)
+    pt = torch.zeros((B, max_pages), dtype=torch.int32, device=dev)
+    cache = Q.Cache(dummy, dummy, meta, pt, torch.from_numpy(lens).to(dev))
+    scd = torch.from_numpy(sc).to(dev)
+    for k_pages in (1, 256, 4097):
+        idx = torch.full((B, H, k_pages), -7, dtype=torch.int32, device=dev)
+        keff = torch.full((B,), -7, dtype=torch.int32, device=dev)
+        Q.quest_topk(cache, scd, k_pages, idx, keff)
+        want, want_keff = O.topk(sc, lens, S, k_pages)
+        assert np.array_equal(keff.cpu().numpy(), want_keff)
+        assert np.array_equal(idx.cpu().numpy(), want), (max_pages, k_pages)
+
+
 def test_sparse_decode_against_oracle(ragged):
     w, table, N, k_pool, v_pool, q, lens, layer = ragged
     meta = O.build_meta(k_pool, table, lens)
