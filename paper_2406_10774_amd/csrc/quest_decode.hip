@@ -20,6 +20,7 @@
 // read), far below the machine balance, so there is no MFMA here: the kernel is
 // bound by how fast HBM delivers the 8 KiB per selected (page, head).
 #include "quest_common.h"
+#include "quest_decode_core.h"
 #include "quest_team.h"
 
 #include <cmath>
@@ -31,9 +32,6 @@ namespace {
 
 constexpr int kDecWaves = 4;
 constexpr int kDecThreads = kDecWaves * kWave;
-constexpr float kNegBig = -1.0e30f;  // "no token yet": finite, so exp2(m - m) never sees inf - inf
-constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLn2 = 0.6931471805599453f;
 
 struct DecodeArgs {
   const char* k_pool;
@@ -53,88 +51,6 @@ struct DecodeArgs {
   int force_device_fences;  // debug: take the cross-die exchange path
   float scale_log2;         // sm_scale * log2(e)
 };
-
-struct PageRegs {
-  uint4 k[4], v[4];
-  int n_valid;
-};
-
-__device__ __forceinline__ float lo(uint32_t h2) {
-  return (float)__builtin_bit_cast(half2_t, h2)[0];
-}
-__device__ __forceinline__ float hi(uint32_t h2) {
-  return (float)__builtin_bit_cast(half2_t, h2)[1];
-}
-
-struct Softmax {
-  float m, l, acc[8];
-};
-
-__device__ __forceinline__ void load_page(PageRegs& r, const DecodeArgs& a, int h, int seq_len,
-                                          int logical_page, int phys, int lane) {
-  const size_t off = ((size_t)phys * a.num_heads + h) * kBlockBytes + lane * 16;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) r.k[i] = ld16(a.k_pool + off + i * 1024);
-#pragma unroll
-  for (int i = 0; i < 4; ++i) r.v[i] = ld16(a.v_pool + off + i * 1024);
-  r.n_valid = min(kPageSize, seq_len - logical_page * kPageSize);
-}
-
-__device__ __forceinline__ void fold_page(Softmax& st, PageRegs& r, const uint4 qv, float scale_log2,
-                                          int grp) {
-  float z[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) z[i] = row16_sum(dot8(qv, r.k[i], 0.f)) * scale_log2;
-  if (r.n_valid < kPageSize) {  // partial last page: stale slots contribute nothing
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if (grp + 4 * i >= r.n_valid) {
-        z[i] = -INFINITY;
-        r.v[i] = make_uint4(0, 0, 0, 0);
-      }
-    }
-  }
-  const float m_new = fmaxf(fmaxf(st.m, fmaxf(z[0], z[1])), fmaxf(z[2], z[3]));
-  const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
-  float p[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) p[i] = __builtin_amdgcn_exp2f(z[i] - m_new);
-  st.l = st.l * alpha + ((p[0] + p[1]) + (p[2] + p[3]));
-#pragma unroll
-  for (int j = 0; j < 8; ++j) st.acc[j] *= alpha;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    st.acc[0] += p[i] * lo(r.v[i].x);
-    st.acc[1] += p[i] * hi(r.v[i].x);
-    st.acc[2] += p[i] * lo(r.v[i].y);
-    st.acc[3] += p[i] * hi(r.v[i].y);
-    st.acc[4] += p[i] * lo(r.v[i].z);
-    st.acc[5] += p[i] * hi(r.v[i].z);
-    st.acc[6] += p[i] * lo(r.v[i].w);
-    st.acc[7] += p[i] * hi(r.v[i].w);
-  }
-  st.m = m_new;
-}
-
-// merge the state held by lane ^ mask into this lane's
-__device__ __forceinline__ void merge_lanes(Softmax& st, int mask) {
-  const float m_o = __shfl_xor(st.m, mask);
-  const float l_o = __shfl_xor(st.l, mask);
-  const float m_n = fmaxf(st.m, m_o);
-  const float a = __builtin_amdgcn_exp2f(st.m - m_n);
-  const float b = __builtin_amdgcn_exp2f(m_o - m_n);
-  st.l = st.l * a + l_o * b;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) st.acc[j] = st.acc[j] * a + __shfl_xor(st.acc[j], mask) * b;
-  st.m = m_n;
-}
-
-__device__ __forceinline__ void store_out(void* out, int out_is_fp16, size_t idx, float v) {
-  if (out_is_fp16)
-    reinterpret_cast<_Float16*>(out)[idx] = (_Float16)v;
-  else
-    reinterpret_cast<float*>(out)[idx] = v;
-}
 
 // Grid is one-dimensional and die-aware: work-groups whose ids are equal modulo
 // 8 run on the same die (round-robin placement), and
@@ -198,17 +114,17 @@ __global__ __launch_bounds__(kDecThreads) void decode_split_kernel(const DecodeA
     PageRegs ra, rb;
     int j = 0;
     int lp = __builtin_amdgcn_readlane(lp_v, 0);
-    if (lp >= 0) load_page(ra, a, h, seq_len, lp, __builtin_amdgcn_readlane(ph_v, 0), lane);
+    if (lp >= 0) load_page(ra, a.k_pool, a.v_pool, a.num_heads, h, seq_len, lp, __builtin_amdgcn_readlane(ph_v, 0), lane);
     while (lp >= 0) {
       int lp_b = -1;
       if (j + 1 < n_here) lp_b = __builtin_amdgcn_readlane(lp_v, j + 1);
-      if (lp_b >= 0) load_page(rb, a, h, seq_len, lp_b, __builtin_amdgcn_readlane(ph_v, j + 1), lane);
+      if (lp_b >= 0) load_page(rb, a.k_pool, a.v_pool, a.num_heads, h, seq_len, lp_b, __builtin_amdgcn_readlane(ph_v, j + 1), lane);
       fold_page(st, ra, qv, a.scale_log2, grp);
       if (lp_b < 0) break;
       j += 2;
       lp = -1;
       if (j < n_here) lp = __builtin_amdgcn_readlane(lp_v, j);
-      if (lp >= 0) load_page(ra, a, h, seq_len, lp, __builtin_amdgcn_readlane(ph_v, j), lane);
+      if (lp >= 0) load_page(ra, a.k_pool, a.v_pool, a.num_heads, h, seq_len, lp, __builtin_amdgcn_readlane(ph_v, j), lane);
       fold_page(st, rb, qv, a.scale_log2, grp);
     }
   }

@@ -19,179 +19,24 @@
 // needs a single barrier, and same-digit lanes are combined into one LDS atomic
 // in the first pass executed, where nearly all keys hit the same few bins.
 #include "quest_common.h"
+#include "quest_topk_core.h"
 
 namespace quest {
 
 namespace {
-
-__device__ __forceinline__ uint32_t score_key(float s) {
-  uint32_t u = __builtin_bit_cast(uint32_t, s);
-  if (u == 0x80000000u) u = 0;  // -0 ranks equal to +0
-  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
-// Inclusive prefix sum over the 64 lanes: DPP row shifts inside each 16-lane
-// row, then the totals of the preceding rows.
-__device__ __forceinline__ int wave_incl_scan(int v, int lane) {
-  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);  // row_shr:1
-  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);  // row_shr:2
-  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);  // row_shr:4
-  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);  // row_shr:8
-  const int r0 = __builtin_amdgcn_readlane(v, 15);
-  const int r1 = __builtin_amdgcn_readlane(v, 31);
-  const int r2 = __builtin_amdgcn_readlane(v, 47);
-  const int row = lane >> 4;
-  return v + (row >= 1 ? r0 : 0) + (row >= 2 ? r1 : 0) + (row >= 3 ? r2 : 0);
-}
-
-// Scan the 256-bin histogram from the top bin down for the bin that holds the
-// need-th largest key.  Lane l owns bins 255-4l .. 252-4l.  Every lane returns
-// the same (bin, keys above the bin, keys in the bin).
-struct BinHit {
-  int bin, above, count;
-};
-__device__ __forceinline__ BinHit find_bin(const uint32_t* hist, int need, int lane) {
-  const int top = 255 - 4 * lane;
-  const int c0 = hist[top], c1 = hist[top - 1], c2 = hist[top - 2], c3 = hist[top - 3];
-  const int tot = c0 + c1 + c2 + c3;
-  const int incl = wave_incl_scan(tot, lane);
-  int above = incl - tot;
-  const bool mine = above < need && need <= incl;
-  int bin = top, count = c0;
-  if (need > above + c0) {
-    above += c0, bin = top - 1, count = c1;
-    if (need > above + c1) {
-      above += c1, bin = top - 2, count = c2;
-      if (need > above + c2) above += c2, bin = top - 3, count = c3;
-    }
-  }
-  const int src = __ffsll((long long)__ballot(mine)) - 1;  // exactly one lane
-  BinHit r;
-  r.bin = __builtin_amdgcn_readlane(bin, src);
-  r.above = __builtin_amdgcn_readlane(above, src);
-  r.count = __builtin_amdgcn_readlane(count, src);
-  return r;
-}
 
 template <int kThreads, int kItems>
 __global__ __launch_bounds__(kThreads) void topk_kernel(
     const float* __restrict__ scores, const int32_t* __restrict__ seq_lens,
     int32_t* __restrict__ topk_idx, int32_t* __restrict__ k_eff, int num_heads, int max_pages,
     int k_pages) {
-  constexpr int kWaves = kThreads / kWave;
-  __shared__ uint32_t hist[4][256];
-  __shared__ int wave_tot[kWaves];
-  __shared__ uint32_t vote;  // != 0: some key's top byte differs from page 0's
-
+  __shared__ TopkShared<kThreads> sm;
   const int h = blockIdx.x;
   const int b = blockIdx.y;
-  const int tid = threadIdx.x;
-  const int lane = lane_id();
-  const int wave = tid >> 6;
-  const float* row = scores + ((size_t)b * num_heads + h) * max_pages;
-  int32_t* out = topk_idx + ((size_t)b * num_heads + h) * k_pages;
-
-  // issue every load first: this thread's scores (entries past the valid pages
-  // are inside the row, so reading them is safe; they are masked below), the
-  // score of page 0 as the vote's reference, and the sequence length
-  const int base = tid * kItems;
-  float raw[kItems];
-#pragma unroll
-  for (int j = 0; j < kItems; ++j) raw[j] = base + j < max_pages ? row[base + j] : 0.f;
-  const float raw0 = row[0];
-  const int seq_len = seq_lens[b];
-
-  for (int i = tid; i < 4 * 256; i += kThreads) (&hist[0][0])[i] = 0;
-  if (tid == 0) vote = 0;
-  __syncthreads();
-
-  const int num_pages = (seq_len + kPageSize - 1) / kPageSize;
-  const int K = min(k_pages, num_pages);
-  if (h == 0 && tid == 0 && k_eff != nullptr) k_eff[b] = K;
-  if (K == num_pages) {  // everything is selected: identity list, padded with -1
-    for (int i = tid; i < k_pages; i += kThreads) out[i] = i < K ? i : -1;
-    return;
-  }
-
-  uint32_t key[kItems];
-  bool valid[kItems];
-  const uint32_t ref_top = score_key(raw0) & 0xff000000u;
-  bool differs = false;
-#pragma unroll
-  for (int j = 0; j < kItems; ++j) {
-    key[j] = score_key(raw[j]);
-    valid[j] = base + j < num_pages;
-    differs |= valid[j] && (key[j] & 0xff000000u) != ref_top;
-  }
-  if (__ballot(differs) != 0 && lane == 0) vote = 1;
-  __syncthreads();
-  const bool skip_first = vote == 0;
-
-  // ---- radix select.  Invariant: the selection is every key whose bits above
-  // `shift + 8` ... are greater than `prefix`'s, plus `need` of the keys that
-  // match `prefix` on the bits decided so far.
-  uint32_t prefix = skip_first ? ref_top : 0u;
-  int need = K;
-  int decided_shift = skip_first ? 24 : 32;  // bits [decided_shift, 32) of the threshold are known
-  bool first_pass = true;
-#pragma unroll
-  for (int pass = 0; pass < 4; ++pass) {
-    if (pass == 0 && skip_first) continue;
-    const int shift = 24 - 8 * pass;
-    const uint32_t high_mask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
-    uint32_t* hp = hist[pass];
-#pragma unroll
-    for (int j = 0; j < kItems; ++j) {
-      const bool act = valid[j] && (key[j] & high_mask) == prefix;
-      const uint32_t digit = (key[j] >> shift) & 255u;
-      if (first_pass) {
-        // most lanes carry the same digit here: one atomic for all of them
-        const uint32_t dd = act ? digit : 0xffffffffu;
-        const uint32_t d0 = __builtin_amdgcn_readfirstlane(dd);
-        const unsigned long long same = __ballot(dd == d0);
-        if (d0 != 0xffffffffu && lane == __ffsll((long long)same) - 1)
-          atomicAdd(&hp[d0], (uint32_t)__popcll(same));
-        if (act && dd != d0) atomicAdd(&hp[digit], 1u);
-      } else if (act) {
-        atomicAdd(&hp[digit], 1u);
-      }
-    }
-    first_pass = false;
-    __syncthreads();
-    const BinHit hit = find_bin(hp, need, lane);
-    prefix |= (uint32_t)hit.bin << shift;
-    need -= hit.above;
-    decided_shift = shift;
-    if (need == hit.count) break;  // the whole bin is selected: no need to split it further
-  }
-
-  // ---- emit in page order.  key > bin: selected; key in bin: the first `need`.
-  const uint32_t T = prefix >> decided_shift;  // decided_shift <= 24
-  int n_gt = 0, n_eq = 0;
-  bool gt[kItems], eq[kItems];
-#pragma unroll
-  for (int j = 0; j < kItems; ++j) {
-    const uint32_t kd = key[j] >> decided_shift;
-    gt[j] = valid[j] && kd > T;
-    eq[j] = valid[j] && kd == T;
-    n_gt += gt[j];
-    n_eq += eq[j];
-  }
-  const int packed = n_gt | (n_eq << 16);  // rows handled here have fewer than 2^16 pages
-  const int incl = wave_incl_scan(packed, lane);
-  if (lane == kWave - 1) wave_tot[wave] = incl;
-  __syncthreads();
-  int before = incl - packed;
-  for (int w = 0; w < kWaves; ++w)
-    if (w < wave) before += wave_tot[w];
-  int gt_before = (uint32_t)before & 0xffffu, eq_before = (uint32_t)before >> 16;
-#pragma unroll
-  for (int j = 0; j < kItems; ++j) {
-    const bool sel = gt[j] || (eq[j] && eq_before < need);
-    if (sel) out[gt_before + min(eq_before, need)] = base + j;
-    gt_before += gt[j];
-    eq_before += eq[j];
-  }
+  const size_t bh = (size_t)b * num_heads + h;
+  topk_block<kThreads, kItems, false>(sm, scores + bh * max_pages, seq_lens + b, max_pages, k_pages,
+                                      topk_idx + bh * k_pages,
+                                      (h == 0 && k_eff != nullptr) ? k_eff + b : nullptr);
 }
 
 // Fallback for rows too long for register-resident keys: keys are re-read from
