@@ -11,7 +11,8 @@
  *     after prefill :  quest_build_meta
  *     every token   :  quest_append_meta -> quest_estimate -> quest_topk
  *                      -> quest_sparse_decode
- *                      (quest_append_estimate fuses the first two launches)
+ *                      (quest_append_estimate fuses the first two launches,
+ *                       quest_decode_step all of them)
  *
  * Conventions for every entry point
  *   - All data pointers are DEVICE pointers owned by the caller.  The library
@@ -148,6 +149,30 @@ int quest_topk(const quest_cache* cache, const float* scores, int32_t k_pages,
 int quest_sparse_decode(const quest_cache* cache, const void* q, const int32_t* topk_idx,
                         int32_t k_pages, float sm_scale, void* out, int32_t out_is_fp16,
                         float* lse, void* workspace, size_t workspace_bytes, void* stream);
+
+/* The whole decode step of one layer in a single launch (Algorithm 1 and
+ * Figure 5): quest_append_estimate (quest_estimate if k_new == NULL), then
+ * quest_topk, then quest_sparse_decode with the list just selected.  k_pool /
+ * v_pool / meta / scores / topk_idx / k_eff receive exactly what those calls
+ * would write, bit for bit; out and lse are the same attention result,
+ * accumulated over a different split of the page list (so equal within fp32
+ * rounding, not bit for bit).  scores and topk_idx are outputs and also the
+ * buffers the phases hand to each other, so they must be provided.
+ * workspace: at least quest_step_workspace_bytes(cache, k_pages) bytes,
+ * zero-filled once after allocation (same rule as for quest_sparse_decode;
+ * one buffer of max(both sizes) may serve both calls); calls sharing a
+ * workspace must not overlap in time.  The 32-bit word at byte offset 4 of the
+ * workspace is a sticky status: 0 = every launch so far completed all its work;
+ * non-zero = a launch left work undone (a compute die received no work-group,
+ * or an internal bounded wait expired) and its outputs must not be used.
+ * On devices other than the 256-CU MI355X, or for max_pages_per_seq > 8192,
+ * the call runs the three launches named above instead. */
+int quest_step_workspace_bytes(const quest_cache* cache, int32_t k_pages, size_t* out_bytes);
+int quest_decode_step(const quest_cache* cache, const void* k_new, const void* v_new,
+                      int32_t k_pool_write, const void* q, int32_t k_pages, float sm_scale,
+                      float* scores, int32_t* topk_idx, int32_t* k_eff, void* out,
+                      int32_t out_is_fp16, float* lse, void* workspace, size_t workspace_bytes,
+                      void* stream);
 
 /* Human-readable description of the last error on the calling thread.  Host
  * string owned by the library, valid until the thread's next failing call. */

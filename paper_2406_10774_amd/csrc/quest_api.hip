@@ -166,4 +166,50 @@ int quest_sparse_decode(const quest_cache* cache, const void* q, const int32_t* 
                               workspace, (hipStream_t)stream);
 }
 
+int quest_step_workspace_bytes(const quest_cache* cache, int32_t k_pages, size_t* out_bytes) {
+  int r = check_cache(cache, "quest_step_workspace_bytes");
+  if (r != QUEST_OK) return r;
+  if (out_bytes == nullptr) {
+    set_error("quest_step_workspace_bytes: out_bytes is NULL");
+    return QUEST_ERR_NULL;
+  }
+  if (k_pages < 1) {
+    set_error("quest_step_workspace_bytes: k_pages must be >= 1 (got %d)", k_pages);
+    return QUEST_ERR_SHAPE;
+  }
+  *out_bytes = step_workspace_bytes(*cache, k_pages);
+  return QUEST_OK;
+}
+
+int quest_decode_step(const quest_cache* cache, const void* k_new, const void* v_new,
+                      int32_t k_pool_write, const void* q, int32_t k_pages, float sm_scale,
+                      float* scores, int32_t* topk_idx, int32_t* k_eff, void* out,
+                      int32_t out_is_fp16, float* lse, void* workspace, size_t workspace_bytes,
+                      void* stream) {
+  int r = check_cache(cache, "quest_decode_step");
+  if (r != QUEST_OK) return r;
+  if (cache->k_pool == nullptr || cache->v_pool == nullptr || cache->meta == nullptr ||
+      q == nullptr || scores == nullptr || topk_idx == nullptr || out == nullptr) {
+    set_error("quest_decode_step: k_pool, v_pool, meta, q, scores, topk_idx and out must not be NULL");
+    return QUEST_ERR_NULL;
+  }
+  if (k_new != nullptr && k_pool_write && v_new == nullptr) {
+    set_error("quest_decode_step: k_pool_write needs v_new");
+    return QUEST_ERR_NULL;
+  }
+  if (k_pages < 1) {
+    set_error("quest_decode_step: k_pages must be >= 1 (got %d)", k_pages);
+    return QUEST_ERR_SHAPE;
+  }
+  const size_t need = step_workspace_bytes(*cache, k_pages);
+  if (workspace == nullptr || workspace_bytes < need) {
+    set_error("quest_decode_step: workspace of %zu bytes needed, %zu given", need,
+              workspace ? workspace_bytes : (size_t)0);
+    return QUEST_ERR_WORKSPACE;
+  }
+  return launch_decode_step(*cache, k_new, v_new, k_pool_write != 0, q, k_pages, sm_scale, scores,
+                            topk_idx, k_eff, out, out_is_fp16 != 0, lse, workspace,
+                            (hipStream_t)stream);
+}
+
 }  // extern "C"

@@ -117,7 +117,7 @@ __device__ __forceinline__ void topk_block(TopkShared<kThreads>& sm, const float
   }
   if (__ballot(differs) != 0 && lane == 0) vote = 1;
   __syncthreads();
-  const bool skip_first = vote == 0;
+  const bool skip_first = __builtin_amdgcn_readfirstlane(vote) == 0;  // uniform: barriers follow
 
   // ---- radix select.  Invariant: the selection is every key whose bits above
   // `shift + 8` ... are greater than `prefix`'s, plus `need` of the keys that

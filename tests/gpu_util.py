@@ -83,6 +83,30 @@ class Layer:
         o = out.cpu().numpy() if not fp16_out else self.np16(out)
         return o, (lse.cpu().numpy() if want_lse else None)
 
+    def step(self, k_new, v_new, q, k_pages, sm_scale=None, write=True):
+        """The whole decode step through the single-launch entry point."""
+        torch = self.torch
+        sm_scale = 1.0 / math.sqrt(self.D) if sm_scale is None else sm_scale
+        if getattr(self, "_step_ws_k", None) != k_pages:
+            nbytes = Q.quest_step_workspace_bytes(self.cache, k_pages)
+            self._step_ws = torch.zeros(max(nbytes, 8) // 4, dtype=torch.int32, device=self.dev)
+            self._step_ws_k = k_pages
+        idx = torch.full((self.B, self.H, k_pages), -7, dtype=torch.int32, device=self.dev)
+        keff = torch.full((self.B,), -7, dtype=torch.int32, device=self.dev)
+        out = torch.full((self.B, self.H, self.D), float("nan"), dtype=torch.float32, device=self.dev)
+        lse = torch.full((self.B, self.H), float("nan"), dtype=torch.float32, device=self.dev)
+        self.scores.fill_(float("nan"))
+        Q.quest_decode_step(self.cache, None if k_new is None else self.half(k_new),
+                            None if v_new is None else self.half(v_new), write, self.half(q),
+                            k_pages, sm_scale, self.scores, idx, out, self._step_ws, k_eff=keff,
+                            lse=lse)
+        torch.cuda.synchronize()
+        status = int(self._step_ws[1].item())
+        assert status == 0, f"decode step left work undone (status {status})"
+        assert int(self._step_ws[0].item()) == 0          # counters re-armed
+        return (self.scores.cpu().numpy(), idx.cpu().numpy(), keff.cpu().numpy(),
+                out.cpu().numpy(), lse.cpu().numpy())
+
     def np16(self, t):
         return t.view(self.torch.int16).cpu().numpy().view(np.float16)
 

@@ -95,3 +95,57 @@ def test_config1_full_size_chain_identity_table():
 
 def test_config1_full_size_chain_shuffled_pages():
     run_chain(synth.workload(1), steps=18, permute=True)   # step 17 opens nothing new, 1..16 fill page 2048
+
+
+def run_single_launch_steps(w, steps, permute):
+    """quest_decode_step against the separate calls (bit-equal metadata, pools, scores
+    and page list) and against the oracle (attention within tolerance)."""
+    from gpu_util import Layer
+    S, D = w.page_size, w.head_dim
+    table, N = synth.make_page_table(w, permute=permute)
+    k_pool, v_pool, _ = synth.fill_pools(w, table, N)
+    lens = np.array(w.seq_lens, np.int32)
+    one = Layer(k_pool, v_pool, table, lens)            # single launch
+    ref = Layer(k_pool, v_pool, table, lens)            # separate calls
+    one.build_meta()
+    ref.build_meta()
+    scale = 1 / math.sqrt(D)
+    cur = lens.copy()
+    for step in range(steps):
+        q = synth.gen_query(w, step)
+        k_new, v_new = synth.gen_new_token(w, step)
+        append = step % 3 != 2                          # every third step: no new token
+        if append:
+            cur += 1
+            one.set_seq_lens(cur)
+            ref.set_seq_lens(cur)
+            ref.append(k_new, v_new, write=True)
+            O.append_kv(k_pool, v_pool, k_new, v_new, table, cur)
+        sc1, idx1, keff1, out1, lse1 = one.step(k_new if append else None,
+                                                v_new if append else None, q, w.k_pages)
+        sc0 = ref.estimate(q)
+        idx0, keff0 = ref.topk(w.k_pages)
+        for b in range(w.batch):
+            P = -(-int(cur[b]) // S)
+            assert np.array_equal(sc1[b, :, :P].view(np.uint32), sc0[b, :, :P].view(np.uint32)), step
+        assert np.array_equal(idx1, idx0) and np.array_equal(keff1, keff0), step
+        want, want_lse = O.sparse_decode(k_pool, v_pool, q, table, cur, idx1, scale)
+        assert np.abs(out1 - want).max() <= ATTN_TOL, step
+        assert np.abs(lse1 - want_lse).max() <= ATTN_TOL, step
+    assert np.array_equal(one.np16(one.meta).view(np.uint16), ref.np16(ref.meta).view(np.uint16))
+    assert np.array_equal(one.np16(one.k_pool).view(np.uint16), ref.np16(ref.k_pool).view(np.uint16))
+    assert np.array_equal(one.np16(one.v_pool).view(np.uint16), ref.np16(ref.v_pool).view(np.uint16))
+
+
+def test_single_launch_step_config0():
+    run_single_launch_steps(synth.workload(0), steps=6, permute=True)
+
+
+def test_single_launch_step_ragged_batch():
+    w = synth.Workload(92, "ragged-step", 5, 3, (1, 16 * 3 + 7, 16 * 203 + 5, 16 * 64, 16 * 130 + 15),
+                       token_budget=16 * 24, planted_per_head=4, decode_steps=24)
+    run_single_launch_steps(w, steps=20, permute=True)
+
+
+def test_single_launch_step_config1_full_size():
+    run_single_launch_steps(synth.workload(1), steps=4, permute=False)
