@@ -9,7 +9,7 @@ namespace quest {
 
 #if defined(__HIPCC__)
 
-constexpr int kEstIters = 4;                     // wave-wide load pairs per wave
+constexpr int kEstIters = 4;                     // wave-wide load pairs per wave (stand-alone kernel)
 constexpr int kEstPagesPerWave = 4 * kEstIters;  // 16
 
 // kAppend: the wave that owns the newest token's page first performs the
@@ -29,9 +29,10 @@ struct EstimateArgs {
   int k_pool_write;
 };
 
-// One wave scores the kEstPagesPerWave logical pages starting at `base` of
-// (sequence b, head h).
-template <bool kAppend>
+// One wave scores the 4 * kIters logical pages starting at `base` of (sequence b,
+// head h): DPP row g takes pages base + kIters*g .. + kIters - 1, one per
+// wave-wide load pair.
+template <bool kAppend, int kIters = kEstIters>
 __device__ __forceinline__ void estimate_wave(const EstimateArgs& a, int b, int h, int base) {
   char* __restrict__ meta = a.meta;
   const char* __restrict__ q = a.q;
@@ -45,7 +46,7 @@ __device__ __forceinline__ void estimate_wave(const EstimateArgs& a, int b, int 
   char* __restrict__ v_pool = a.v_pool;
   const int k_pool_write = a.k_pool_write;
   const int lane = lane_id();
-  const int grp = lane >> 4;  // DPP row: pages base + 4*grp + it
+  const int grp = lane >> 4;  // DPP row: pages base + kIters*grp + it
   const int c = lane & 15;    // channels 8c..8c+7
   const size_t bh = (size_t)b * num_heads + h;
 
@@ -53,20 +54,20 @@ __device__ __forceinline__ void estimate_wave(const EstimateArgs& a, int b, int 
   // max_pages entries); whether a page holds tokens is decided afterwards
   const int32_t* pt = page_table + (size_t)b * max_pages;
   const int seq_len = seq_lens[b];
-  int phys[kEstIters];
+  int phys[kIters];
 #pragma unroll
-  for (int it = 0; it < kEstIters; ++it) {
-    const int p = base + 4 * grp + it;
+  for (int it = 0; it < kIters; ++it) {
+    const int p = base + kIters * grp + it;
     phys[it] = p < max_pages ? pt[p] : 0;
   }
   const uint4 qv = ld16(q + bh * (kHeadDim * 2) + c * 16);
   const int num_pages = (seq_len + kPageSize - 1) / kPageSize;
   if (base >= num_pages) return;
 
-  uint4 mn[kEstIters], mx[kEstIters];
+  uint4 mn[kIters], mx[kIters];
 #pragma unroll
-  for (int it = 0; it < kEstIters; ++it) {
-    const int p = base + 4 * grp + it;
+  for (int it = 0; it < kIters; ++it) {
+    const int p = base + kIters * grp + it;
     mn[it] = make_uint4(0, 0, 0, 0);
     mx[it] = make_uint4(0, 0, 0, 0);
     if (p < num_pages) {
@@ -79,13 +80,13 @@ __device__ __forceinline__ void estimate_wave(const EstimateArgs& a, int b, int 
   if (kAppend) {
     const int pos = seq_len - 1;
     const int last = pos / kPageSize;
-    if (last >= base && last < base + kEstPagesPerWave) {  // wave-uniform
+    if (last >= base && last < base + 4 * kIters) {  // wave-uniform
       const int slot = pos - last * kPageSize;
       const uint4 kn = ld16(k_new + bh * (kHeadDim * 2) + c * 16);
       const uint4 key = order_key8(kn);
 #pragma unroll
-      for (int it = 0; it < kEstIters; ++it) {
-        if (base + 4 * grp + it == last) {
+      for (int it = 0; it < kIters; ++it) {
+        if (base + kIters * grp + it == last) {
           const size_t ph = (size_t)phys[it] * num_heads + h;
           if (k_pool_write) {
             const size_t off = ph * kBlockBytes + (size_t)slot * (kHeadDim * 2) + c * 16;
@@ -116,7 +117,7 @@ __device__ __forceinline__ void estimate_wave(const EstimateArgs& a, int b, int 
 
   float keep = 0.f;
 #pragma unroll
-  for (int it = 0; it < kEstIters; ++it) {
+  for (int it = 0; it < kIters; ++it) {
     uint4 sel;
     sel.x = (mn[it].x & neg.x) | (mx[it].x & ~neg.x);
     sel.y = (mn[it].y & neg.y) | (mx[it].y & ~neg.y);
@@ -126,8 +127,8 @@ __device__ __forceinline__ void estimate_wave(const EstimateArgs& a, int b, int 
     if (c == it) keep = s;
   }
   // lanes c < 4 of each row hold 4 consecutive pages: 16 consecutive floats per wave
-  const int p = base + 4 * grp + c;
-  if (c < kEstIters && p < num_pages) scores[bh * max_pages + p] = keep;
+  const int p = base + kIters * grp + c;
+  if (c < kIters && p < num_pages) scores[bh * max_pages + p] = keep;
 }
 
 #endif  // __HIPCC__

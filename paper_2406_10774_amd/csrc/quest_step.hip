@@ -12,7 +12,7 @@
 //
 // Scheme.  A (sequence, head) pair is an "item"; item i belongs to die i % 8.
 // Each die has a queue (one ticket counter) of tasks in a fixed order: first
-// every estimate task of its items (128 pages each: 8 waves x 16 pages), then
+// every estimate task of its items (64 or 128 pages each), then
 // every attention task (a slice of the selected-page list).  Work-groups are
 // persistent: a work-group reads the id of the die it really runs on and
 // serves that die's queue until it is empty.  Everything the work-groups of an
@@ -46,7 +46,6 @@ namespace {
 
 constexpr int kStepThreads = 512;
 constexpr int kStepWaves = kStepThreads / kWave;              // 8
-constexpr int kStepEstPages = kStepWaves * kEstPagesPerWave;  // 128 pages per estimate task
 constexpr int kNumDies = 8;
 constexpr int kSlotWords = 64;  // 256-byte slots of uint32 words
 // workspace words: slot 0 = {leavers, status}; slots 1..8 = die queues;
@@ -68,10 +67,14 @@ struct StepArgs {
   float* part_acc;   // [items * dec_tasks][D]
   float* part_ml;    // [items * dec_tasks][2]
   int batch, k_pages, out_is_fp16;
-  int est_tasks;     // E: estimate tasks per item = ceil(max_pages / 128)
+  int est_iters;     // pages per DPP row in an estimate task (2 or 4): a task covers 32 * est_iters pages
+  int est_tasks;     // E: estimate tasks per item = ceil(max_pages / (32 * est_iters))
   int dec_tasks;     // Dn: attention tasks per item
   int pages_per_wave;  // list positions per wave in an attention task (<= 64)
   float scale_log2;
+#ifdef QUEST_STEP_TRACE
+  unsigned long long* trace;
+#endif
 };
 
 __device__ __forceinline__ uint32_t word_add(uint32_t* p, uint32_t v) {
@@ -83,6 +86,18 @@ __device__ __forceinline__ uint32_t word_load(const uint32_t* p) {
 __device__ __forceinline__ void word_set(uint32_t* p, uint32_t v) {
   __hip_atomic_exchange(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+
+#ifdef QUEST_STEP_TRACE
+#define STEP_TRACE(slot)                                                              \
+  do {                                                                                \
+    if (threadIdx.x == 0 && a.trace && a.trace[(size_t)blockIdx.x * 16 + (slot)] == 0) \
+      a.trace[(size_t)blockIdx.x * 16 + (slot)] = wall_clock64();                     \
+  } while (0)
+#else
+#define STEP_TRACE(slot) \
+  do {                   \
+  } while (0)
+#endif
 
 struct StepShared {
   TopkShared<kStepThreads> topk;
@@ -115,6 +130,7 @@ __device__ __forceinline__ void attention_task(const StepArgs& a, StepShared& sm
     }
   }
   __syncthreads();
+  STEP_TRACE(6);
 
   const int list_len = a.k_pages < max_pages ? a.k_pages : max_pages;
   const int begin = chunk * kStepWaves * a.pages_per_wave;
@@ -164,6 +180,7 @@ __device__ __forceinline__ void attention_task(const StepArgs& a, StepShared& sm
     }
   }
 
+  STEP_TRACE(7);
   merge_lanes(st, 16);
   merge_lanes(st, 32);
   if (lane < 16) {
@@ -206,6 +223,7 @@ __device__ __forceinline__ void attention_task(const StepArgs& a, StepShared& sm
   if (tid == 0) sm.u[1] = word_add(state + 2, 1u);
   __syncthreads();
   const bool last = __builtin_amdgcn_readfirstlane(sm.u[1]) == (uint32_t)a.dec_tasks - 1;
+  STEP_TRACE(8);
   __syncthreads();
   if (!last || tid >= kHeadDim) return;
 
@@ -237,6 +255,7 @@ __device__ __forceinline__ void attention_task(const StepArgs& a, StepShared& sm
   }
   store_out(a.out, a.out_is_fp16, (size_t)item * kHeadDim + tid, o / l_all);
   if (tid == 0 && a.lse) a.lse[item] = (mx + __builtin_amdgcn_logf(l_all)) * kLn2;
+  STEP_TRACE(9);
 }
 
 template <int kItems, bool kAppend>
@@ -251,6 +270,7 @@ __global__ __launch_bounds__(kStepThreads, 4) void step_kernel(const StepArgs a)
   const uint32_t n_est = (uint32_t)my_items * a.est_tasks;
   const uint32_t total = n_est + (uint32_t)my_items * a.dec_tasks;
   uint32_t* queue = a.words + (1 + die) * kSlotWords;
+  STEP_TRACE(0);
 
   for (;;) {
     if (tid == 0) sm.u[0] = word_add(queue, 1u);
@@ -261,18 +281,24 @@ __global__ __launch_bounds__(kStepThreads, 4) void step_kernel(const StepArgs a)
     __syncthreads();
     if (ticket >= total) break;
     if (ticket < n_est) {
+      STEP_TRACE(1);
       // ---- estimate task (with the insertion of the new token where it falls)
       const int item = (int)(ticket / a.est_tasks) * kNumDies + die;
       const int chunk = (int)(ticket % a.est_tasks);
       const int b = item / num_heads;
       const int h = item - b * num_heads;
       uint32_t* state = a.words + (size_t)(kItemSlot0 + item) * kSlotWords;
-      estimate_wave<kAppend>(a.est, b, h, chunk * kStepEstPages + wave * kEstPagesPerWave);
+      if (a.est_iters == 2)
+        estimate_wave<kAppend, 2>(a.est, b, h, (chunk * kStepWaves + wave) * 8);
+      else
+        estimate_wave<kAppend, 4>(a.est, b, h, (chunk * kStepWaves + wave) * 16);
       wait_stores();
+      STEP_TRACE(2);
       __syncthreads();
       if (tid == 0) sm.u[1] = word_add(state, 1u);
       __syncthreads();
       const bool last = __builtin_amdgcn_readfirstlane(sm.u[1]) == (uint32_t)a.est_tasks - 1;
+      STEP_TRACE(3);
       __syncthreads();
       if (last) {
         topk_block<kStepThreads, kItems, true>(
@@ -282,6 +308,7 @@ __global__ __launch_bounds__(kStepThreads, 4) void step_kernel(const StepArgs a)
         wait_stores();
         __syncthreads();
         if (tid == 0) word_set(state + 1, 1u);
+        STEP_TRACE(4);
         // Every single-lane section in this loop is closed by a barrier before the
         // back-edge.  Without it the compiler may sink the section into the next
         // iteration's single-lane ticket draw and let the other lanes of wave 0 run
@@ -290,6 +317,7 @@ __global__ __launch_bounds__(kStepThreads, 4) void step_kernel(const StepArgs a)
         __syncthreads();
       }
     } else {
+      STEP_TRACE(5);
       const uint32_t t = ticket - n_est;
       const int item = (int)(t / a.dec_tasks) * kNumDies + die;
       const int chunk = (int)(t % a.dec_tasks);
@@ -298,6 +326,7 @@ __global__ __launch_bounds__(kStepThreads, 4) void step_kernel(const StepArgs a)
     }
   }
 
+  STEP_TRACE(10);
   // ---- leave; the last one out checks the queues and re-arms every counter
   if (tid == 0) sm.u[2] = word_add(a.words, 1u);
   __syncthreads();
@@ -321,7 +350,7 @@ int env_int(const char* name, int fallback) {
 }
 
 struct StepPlan {
-  int groups, est_tasks, dec_tasks, pages_per_wave;
+  int groups, est_iters, est_tasks, dec_tasks, pages_per_wave;
   bool fused;
 };
 
@@ -343,7 +372,13 @@ StepPlan plan_step(const quest_cache& c, int k_pages) {
   // the three-launch path.
   p.fused = !disable && cus == 256 && c.max_pages_per_seq <= kStepThreads * 16;
   p.groups = 2 * 256;
-  p.est_tasks = (c.max_pages_per_seq + kStepEstPages - 1) / kStepEstPages;
+  // Estimate tasks of 64 pages: with the queue in item order, the work-groups of
+  // a die first all work on its first items and then on the rest, so the
+  // selection of the first items overlaps with the estimate of the others.
+  static const int est_iters = env_int("QUEST_STEP_EST_ITERS", 2);
+  p.est_iters = est_iters == 4 ? 4 : 2;
+  const int est_pages = kStepWaves * 4 * p.est_iters;
+  p.est_tasks = (c.max_pages_per_seq + est_pages - 1) / est_pages;
   const long items = (long)c.batch * c.num_heads;
   const long list_len = k_pages < c.max_pages_per_seq ? k_pages : c.max_pages_per_seq;
   long ppw = (items * list_len + (long)kStepWaves * p.groups - 1) / ((long)kStepWaves * p.groups);
@@ -416,10 +451,16 @@ int launch_decode_step(const quest_cache& c, const void* k_new, const void* v_ne
   a.batch = c.batch;
   a.k_pages = k_pages;
   a.out_is_fp16 = out_is_fp16;
+  a.est_iters = p.est_iters;
   a.est_tasks = p.est_tasks;
   a.dec_tasks = p.dec_tasks;
   a.pages_per_wave = p.pages_per_wave;
   a.scale_log2 = sm_scale * kLog2e;
+#ifdef QUEST_STEP_TRACE
+  a.trace = std::getenv("QUEST_STEP_TRACE_PTR")
+                ? (unsigned long long*)std::strtoull(std::getenv("QUEST_STEP_TRACE_PTR"), nullptr, 16)
+                : nullptr;
+#endif
   const bool append = k_new != nullptr;
   const int mp = c.max_pages_per_seq;
 #define QUEST_STEP_CASE(I) \
