@@ -99,6 +99,8 @@ def main():
     out = torch.zeros((B, H, D), dtype=torch.float32, device=dev)
     ws_bytes = max(Q.quest_workspace_bytes(caches[0], K), Q.quest_workspace_bytes(caches[0], 0), 4)
     ws = torch.zeros(ws_bytes // 4, dtype=torch.float32, device=dev)
+    ws_step = torch.zeros(max(Q.quest_step_workspace_bytes(caches[0], K), 8) // 4, dtype=torch.int32,
+                          device=dev)
     torch.cuda.synchronize()
     gen_s = time.time() - t0
 
@@ -115,6 +117,10 @@ def main():
         Q.quest_estimate(c, q_all[i], scores)
         Q.quest_topk(c, scores, K, idx, None)
         Q.quest_sparse_decode(c, q_all[i], idx, K, scale, out, None, ws)
+
+    def single_launch_step(i):                            # the whole step in one launch
+        Q.quest_decode_step(caches[i], kn_all[i], vn_all[i], True, q_all[i], K, scale, scores, idx,
+                            out, ws_step)
 
     def dense_step(i):
         c = caches[i]
@@ -165,6 +171,12 @@ def main():
     g_sep = capture(sparse_step_separate, timed)
     g_sep.replay()
     sep_us = time_graph(g_sep, max(3, args.repeats // 2))[0] / args.steps * 1e6
+
+    g_one = capture(single_launch_step, timed)
+    g_one.replay()
+    one_us = time_graph(g_one, max(3, args.repeats // 2))[0] / args.steps * 1e6
+    torch.cuda.synchronize()
+    assert int(ws_step[1].item()) == 0, "quest_decode_step reported unfinished work"
 
     g_dense = capture(dense_step, timed)
     g_dense.replay()
@@ -239,6 +251,7 @@ def main():
         "hbm_gbps": round(gbps, 1), "hbm_frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4),
         "bytes_per_step": int(step_bytes), "us_per_step_gpu_events": round(us_step_events, 3),
         "separate_calls_us_per_step": round(sep_us, 3),
+        "single_launch_us_per_step": round(one_us, 3),
         "dense_us_per_step": round(dense_us, 3),
         "dense_hbm_gbps": round(dense_bytes / (dense_us * 1e-6) / 1e9, 1),
         "speedup_vs_own_dense": round(dense_us / us_step, 3),

@@ -33,6 +33,17 @@ namespace {
 constexpr int kDecWaves = 4;
 constexpr int kDecThreads = kDecWaves * kWave;
 
+#ifdef QUEST_STEP_TRACE
+#define DEC_TRACE(slot)                                                                  \
+  do {                                                                                   \
+    if (threadIdx.x == 0 && a.trace) a.trace[(size_t)blockIdx.x * 16 + (slot)] = wall_clock64(); \
+  } while (0)
+#else
+#define DEC_TRACE(slot) \
+  do {                  \
+  } while (0)
+#endif
+
 struct DecodeArgs {
   const char* k_pool;
   const char* v_pool;
@@ -50,6 +61,9 @@ struct DecodeArgs {
   int per_split;            // ceil(list_len / splits)
   int force_device_fences;  // debug: take the cross-die exchange path
   float scale_log2;         // sm_scale * log2(e)
+#ifdef QUEST_STEP_TRACE
+  unsigned long long* trace;
+#endif
 };
 
 // Grid is one-dimensional and die-aware: work-groups whose ids are equal modulo
@@ -78,6 +92,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_split_kernel(const DecodeA
   const int grp = lane >> 4;
   const int c = lane & 15;
   const uint32_t die = xcc_id();
+  DEC_TRACE(0);
   uint64_t* team_word = a.counters + bh * kTeamWordStride;
   if (a.splits > 1 && threadIdx.x == 0) team_checkin(team_word, die);
 
@@ -110,6 +125,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_split_kernel(const DecodeA
     const int num_pages = (seq_len + kPageSize - 1) / kPageSize;
     if (lp_v >= num_pages) lp_v = -1;
     const int n_here = min(kWave, iters - chunk);
+    if (__builtin_amdgcn_readlane(ph_v, 0) >= 0) DEC_TRACE(1);
 
     PageRegs ra, rb;
     int j = 0;
@@ -130,6 +146,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_split_kernel(const DecodeA
   }
 
   // the four DPP rows of the wave, then the four waves of the group
+  DEC_TRACE(2);
   merge_lanes(st, 16);
   merge_lanes(st, 32);
   if (lane < 16) {
@@ -167,6 +184,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_split_kernel(const DecodeA
     a.part_ml[ps * 2 + 0] = m_tot;
     a.part_ml[ps * 2 + 1] = l_tot;
   }
+  DEC_TRACE(3);
   wait_stores();
   __syncthreads();
   if (t == 0) {
@@ -176,6 +194,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_split_kernel(const DecodeA
   }
   __syncthreads();
   const uint64_t before = sm_before[0] | ((uint64_t)sm_before[1] << 32);
+  DEC_TRACE(4);
   if (!team_is_last(before, a.splits)) return;
   team_acquire(before, a.splits, die, a.force_device_fences);
   if (t == 0) team_reset(team_word);
@@ -210,6 +229,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_split_kernel(const DecodeA
     mx = cm;
   }
   store_out(a.out, a.out_is_fp16, bh * kHeadDim + t, o / l_all);
+  DEC_TRACE(5);
   if (t == 0 && a.lse) a.lse[bh] = (mx + __builtin_amdgcn_logf(l_all)) * kLn2;
 }
 
@@ -284,6 +304,11 @@ int launch_sparse_decode(const quest_cache& c, const void* q, const int32_t* top
   a.out_is_fp16 = out_is_fp16;
   a.lse = lse;
   a.scale_log2 = sm_scale * kLog2e;
+#ifdef QUEST_STEP_TRACE
+  a.trace = std::getenv("QUEST_STEP_TRACE_PTR")
+                ? (unsigned long long*)std::strtoull(std::getenv("QUEST_STEP_TRACE_PTR"), nullptr, 16)
+                : nullptr;
+#endif
   const size_t n_part = (size_t)c.batch * c.num_heads * a.splits;
   a.counters = (uint64_t*)workspace;
   a.part_acc = workspace ? (float*)((char*)workspace + counter_bytes(c)) : nullptr;
