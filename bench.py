@@ -90,7 +90,7 @@ def main():
     for l in range(n_layers):
         kp = k0 if l == 0 else k0.clone()
         vp = v0 if l == 0 else v0.clone()
-        meta = torch.zeros((N, H, 2, D), dtype=torch.float16, device=dev)
+        meta = torch.zeros((H, N, 2, D), dtype=torch.float16, device=dev)
         Q.quest_build_meta(Q.Cache(kp, vp, meta, pt, lens0_dev))
         layers.append((kp, vp, meta))
     caches = [Q.Cache(*layers[i % n_layers], pt, lens_dev[i]) for i in range(n_total)]

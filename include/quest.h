@@ -33,7 +33,8 @@
  *
  * Layouts (row-major, innermost last)
  *   k_pool, v_pool : fp16  [num_phys_pages][num_heads][page_size][head_dim]
- *   meta           : fp16  [num_phys_pages][num_heads][2][head_dim]
+ *   meta           : fp16  [num_heads][num_phys_pages][2][head_dim]  (head-major:
+ *                          the estimate scans all pages of a head)
  *                          [..][0][:] = channel-wise min, [..][1][:] = max
  *   page_table     : int32 [batch][max_pages_per_seq]; logical page p of
  *                          sequence b (tokens [p*S, p*S+S)) -> physical page
@@ -93,7 +94,7 @@ int quest_workspace_bytes(const quest_cache* cache, int32_t k_pages, size_t* out
 
 /* Metadata of every page that holds at least one token (Section 3.4:
  * "maximum and minimum values of each feature dimension of the Key vector"):
- *   meta[phys][h][0][i] = min_j k[j][i],  meta[phys][h][1][i] = max_j k[j][i]
+ *   meta[h][phys][0][i] = min_j k[j][i],  meta[h][phys][1][i] = max_j k[j][i]
  * over the valid tokens j of the page (a partial last page: its first
  * seq_len - p*S slots).  Comparison is by value with -0 ordered below +0, so
  * the result is independent of reduction order and bit-exact.  Entries of

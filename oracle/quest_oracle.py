@@ -11,7 +11,7 @@ fp16 inputs to float64 and accumulate in float64.
 
 Shapes (C order):
   k_pool, v_pool : float16 [N][H][S][D]    N physical pages, S tokens per page
-  meta           : float16 [N][H][2][D]    [..,0,:] = channel-wise min, [..,1,:] = max
+  meta           : float16 [H][N][2][D]    [..,0,:] = channel-wise min, [..,1,:] = max
   page_table     : int32   [B][max_pages]  logical page p of sequence b -> physical page
   seq_lens       : int32   [B]             valid tokens; logical page p holds tokens [pS, pS+S)
   q              : float16 [B][H][D]
@@ -83,10 +83,10 @@ def build_meta(k_pool, page_table, seq_lens, meta_init=None):
     """Metadata of every mapped page: m_i = min_j k_{j,i}, M_i = max_j k_{j,i}
     over the valid tokens j of the page (Section 3.4).
 
-    Returns meta float16 [N][H][2][D]; entries of pages that hold no valid
+    Returns meta float16 [H][N][2][D]; entries of pages that hold no valid
     token keep the value of `meta_init` (zeros if not given)."""
     N, H, S, D = k_pool.shape
-    meta = np.zeros((N, H, 2, D), np.float16) if meta_init is None else meta_init.copy()
+    meta = np.zeros((H, N, 2, D), np.float16) if meta_init is None else meta_init.copy()
     for b in range(len(seq_lens)):
         L = int(seq_lens[b])
         P = num_pages(L, S)
@@ -94,8 +94,8 @@ def build_meta(k_pool, page_table, seq_lens, meta_init=None):
             n = valid_in_page(L, S, p)
             phys = int(page_table[b, p])
             toks = k_pool[phys, :, :n, :]                 # [H][n][D]
-            meta[phys, :, 0, :] = _min_total_order(toks, axis=1)
-            meta[phys, :, 1, :] = _max_total_order(toks, axis=1)
+            meta[:, phys, 0, :] = _min_total_order(toks, axis=1)
+            meta[:, phys, 1, :] = _max_total_order(toks, axis=1)
     return meta
 
 
@@ -111,11 +111,11 @@ def append_meta(meta, k_new, page_table, seq_lens, page_size):
         phys = int(page_table[b, pos // page_size])
         k = k_new[b]                                        # [H][D]
         if pos % page_size == 0:
-            out[phys, :, 0, :] = k
-            out[phys, :, 1, :] = k
+            out[:, phys, 0, :] = k
+            out[:, phys, 1, :] = k
         else:
-            out[phys, :, 0, :] = _min_total_order(np.stack([out[phys, :, 0, :], k]), axis=0)
-            out[phys, :, 1, :] = _max_total_order(np.stack([out[phys, :, 1, :], k]), axis=0)
+            out[:, phys, 0, :] = _min_total_order(np.stack([out[:, phys, 0, :], k]), axis=0)
+            out[:, phys, 1, :] = _max_total_order(np.stack([out[:, phys, 1, :], k]), axis=0)
     return out
 
 
@@ -145,8 +145,8 @@ def estimate(meta, q, page_table, seq_lens, page_size, max_pages=None):
         phys = page_table[b, :P]
         for h in range(H):
             qv = q[b, h].astype(np.float64)                 # [D]
-            m = meta[phys, h, 0, :].astype(np.float64)      # [P][D]
-            M = meta[phys, h, 1, :].astype(np.float64)
+            m = meta[h, phys, 0, :].astype(np.float64)      # [P][D]
+            M = meta[h, phys, 1, :].astype(np.float64)
             U = np.maximum(qv[None, :] * m, qv[None, :] * M)
             scores[b, h, :P] = U.sum(axis=1)
     return scores

@@ -14,7 +14,11 @@ constexpr int kHeadDim = 128;   // D: channels per head
 constexpr int kPageSize = 16;   // S: tokens per page
 constexpr int kWave = 64;
 // One (page, head) block of keys (or of values) is S*D fp16 = 4 KiB = 4 wave-wide
-// 16-byte loads; one metadata entry (min row + max row) is 512 B.
+// 16-byte loads; one metadata entry (min row + max row) is 512 B.  The metadata
+// table is head-major, [H][num_phys_pages]: the estimate scans every page of a
+// head, and consecutive physical pages of one head are then contiguous (with
+// page-major entries the same scan touches 512 B every 16 KiB, measured 25 %
+// slower on MI355X).
 constexpr int kBlockBytes = kPageSize * kHeadDim * 2;
 constexpr int kMetaBytes = 2 * kHeadDim * 2;
 
@@ -122,6 +126,11 @@ __device__ __forceinline__ uint4 shfl_xor16(uint4 v, int mask) {
 }
 
 __device__ __forceinline__ int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// Byte offset of the metadata entry of (physical page, head).
+__device__ __forceinline__ size_t meta_offset(int64_t num_phys_pages, int phys, int h) {
+  return ((size_t)h * (size_t)num_phys_pages + (size_t)phys) * kMetaBytes;
+}
 
 #endif  // __HIPCC__
 

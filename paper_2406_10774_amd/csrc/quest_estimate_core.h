@@ -22,6 +22,7 @@ struct EstimateArgs {
   const int32_t* seq_lens;
   float* scores;
   int num_heads, max_pages;
+  int64_t num_phys_pages;
   const char* k_new;  // kAppend only
   const char* v_new;
   char* k_pool;
@@ -71,7 +72,7 @@ __device__ __forceinline__ void estimate_wave(const EstimateArgs& a, int b, int 
     mn[it] = make_uint4(0, 0, 0, 0);
     mx[it] = make_uint4(0, 0, 0, 0);
     if (p < num_pages) {
-      const char* entry = meta + ((size_t)phys[it] * num_heads + h) * kMetaBytes + c * 16;
+      const char* entry = meta + meta_offset(a.num_phys_pages, phys[it], h) + c * 16;
       mn[it] = ld16(entry);
       mx[it] = ld16(entry + kHeadDim * 2);
     }
@@ -100,7 +101,7 @@ __device__ __forceinline__ void estimate_wave(const EstimateArgs& a, int b, int 
             mn[it] = order_key8(key_min8(order_key8(mn[it]), key));
             mx[it] = order_key8(key_max8(order_key8(mx[it]), key));
           }
-          char* entry = meta + ph * kMetaBytes + c * 16;
+          char* entry = meta + meta_offset(a.num_phys_pages, phys[it], h) + c * 16;
           st16(entry, mn[it]);
           st16(entry + kHeadDim * 2, mx[it]);
         }

@@ -24,7 +24,7 @@ constexpr uint32_t kKeyMin2 = 0x80008000u;  // identity of max
 // [r*1024, r*1024+1024) of the block, 16 bytes per lane.
 __global__ __launch_bounds__(kBuildWaves* kWave) void build_meta_kernel(
     const char* __restrict__ k_pool, char* __restrict__ meta, const int32_t* __restrict__ page_table,
-    const int32_t* __restrict__ seq_lens, int num_heads, int max_pages) {
+    const int32_t* __restrict__ seq_lens, int num_heads, int max_pages, int64_t num_phys_pages) {
   const int b = blockIdx.z;
   const int h = blockIdx.y;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -68,7 +68,7 @@ __global__ __launch_bounds__(kBuildWaves* kWave) void build_meta_kernel(
     mn = key_min8(mn, shfl_xor16(mn, 32));
     mx = key_max8(mx, shfl_xor16(mx, 32));
     // lanes 0..15 store the min row, lanes 16..31 the max row: 512 contiguous bytes
-    char* entry = meta + ((size_t)phys[u] * num_heads + h) * kMetaBytes;
+    char* entry = meta + meta_offset(num_phys_pages, phys[u], h);
     if (lane < 32) st16(entry + lane * 16, order_key8(grp == 0 ? mn : mx));
   }
 }
@@ -78,7 +78,7 @@ __global__ __launch_bounds__(256) void append_meta_kernel(
     char* __restrict__ k_pool, char* __restrict__ v_pool, char* __restrict__ meta,
     const int32_t* __restrict__ page_table, const int32_t* __restrict__ seq_lens,
     const char* __restrict__ k_new, const char* __restrict__ v_new, int batch, int num_heads,
-    int max_pages, int k_pool_write) {
+    int max_pages, int k_pool_write, int64_t num_phys_pages) {
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
   const int bh = t >> 4;
   const int c = t & 15;
@@ -97,7 +97,7 @@ __global__ __launch_bounds__(256) void append_meta_kernel(
     st16(k_pool + off, k);
     st16(v_pool + off, ld16(v_new + (size_t)bh * (kHeadDim * 2) + c * 16));
   }
-  char* entry = meta + ph * kMetaBytes + c * 16;
+  char* entry = meta + meta_offset(num_phys_pages, phys, h) + c * 16;
   if (slot == 0) {  // first token of a page: min = max = k
     st16(entry, k);
     st16(entry + kHeadDim * 2, k);
@@ -117,7 +117,7 @@ int launch_build_meta(const quest_cache& c, hipStream_t s) {
             c.batch);
   hipLaunchKernelGGL(build_meta_kernel, grid, dim3(kBuildWaves * kWave), 0, s,
                      (const char*)c.k_pool, (char*)c.meta, c.page_table, c.seq_lens, c.num_heads,
-                     c.max_pages_per_seq);
+                     c.max_pages_per_seq, c.num_phys_pages);
   return check_launch("quest_build_meta");
 }
 
@@ -127,7 +127,7 @@ int launch_append_meta(const quest_cache& c, const void* k_new, const void* v_ne
   hipLaunchKernelGGL(append_meta_kernel, dim3((threads + 255) / 256), dim3(256), 0, s,
                      (char*)c.k_pool, (char*)c.v_pool, (char*)c.meta, c.page_table, c.seq_lens,
                      (const char*)k_new, (const char*)v_new, c.batch, c.num_heads,
-                     c.max_pages_per_seq, k_pool_write);
+                     c.max_pages_per_seq, k_pool_write, c.num_phys_pages);
   return check_launch("quest_append_meta");
 }
 

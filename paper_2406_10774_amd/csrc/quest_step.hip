@@ -434,6 +434,7 @@ int launch_decode_step(const quest_cache& c, const void* k_new, const void* v_ne
   a.est.scores = scores;
   a.est.num_heads = c.num_heads;
   a.est.max_pages = c.max_pages_per_seq;
+  a.est.num_phys_pages = c.num_phys_pages;
   a.est.k_new = (const char*)k_new;
   a.est.v_new = (const char*)v_new;
   a.est.k_pool = (char*)c.k_pool;

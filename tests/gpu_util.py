@@ -19,7 +19,7 @@ class Layer:
         self.B, self.max_pages = page_table.shape
         self.k_pool = self._to_dev(k_pool)
         self.v_pool = self._to_dev(v_pool)
-        self.meta = torch.zeros((N, H, 2, D), dtype=torch.float16, device=device)
+        self.meta = torch.zeros((H, N, 2, D), dtype=torch.float16, device=device)
         if meta_fill is not None:
             self.meta.fill_(meta_fill)
         self.page_table = torch.from_numpy(np.ascontiguousarray(page_table)).to(device)
@@ -122,8 +122,8 @@ def score_tolerance(meta, q, page_table, seq_lens, S):
         phys = page_table[b, :P]
         for h in range(H):
             qv = q[b, h].astype(np.float64)
-            a = np.abs(qv[None] * meta[phys, h, 0].astype(np.float64))
-            c = np.abs(qv[None] * meta[phys, h, 1].astype(np.float64))
+            a = np.abs(qv[None] * meta[h, phys, 0].astype(np.float64))
+            c = np.abs(qv[None] * meta[h, phys, 1].astype(np.float64))
             tol[b, h, :P] = np.maximum(a, c).sum(-1) * (D * 2.0 ** -24) + 1e-30
     return tol
 

@@ -31,7 +31,7 @@ def run_chain(w, steps, permute):
     meta = O.build_meta(k_pool, table, lens)
     got_meta = layer.build_meta()
     mapped = np.unique(np.concatenate([table[b, :w.pages_of(b)] for b in range(w.batch)]))
-    assert np.array_equal(got_meta[mapped].view(np.uint16), meta[mapped].view(np.uint16))
+    assert np.array_equal(got_meta[:, mapped].view(np.uint16), meta[:, mapped].view(np.uint16))
 
     cur = lens.copy()
     near_ties = 0
@@ -65,7 +65,7 @@ def run_chain(w, steps, permute):
     # metadata and pools maintained over the steps == oracle's
     got_meta = layer.np16(layer.meta)
     mapped = np.unique(np.concatenate([table[b, :-(-int(cur[b]) // S)] for b in range(w.batch)]))
-    assert np.array_equal(got_meta[mapped].view(np.uint16), meta[mapped].view(np.uint16))
+    assert np.array_equal(got_meta[:, mapped].view(np.uint16), meta[:, mapped].view(np.uint16))
     last = np.array([table[b, (int(cur[b]) - 1) // S] for b in range(w.batch)])
     n_last = [(int(cur[b]) - 1) % S + 1 for b in range(w.batch)]
     got_k, got_v = layer.np16(layer.k_pool[torch_index(layer, last)]), \

@@ -42,7 +42,7 @@ def test_build_meta_bit_exact(ragged):
     k2[stale] = np.float16("nan")
     layer.k_pool.copy_(layer.half(k2))
     got = layer.build_meta()
-    want = O.build_meta(k2, table, lens, meta_init=np.full((N, w.num_heads, 2, w.head_dim), 77.0,
+    want = O.build_meta(k2, table, lens, meta_init=np.full((w.num_heads, N, 2, w.head_dim), 77.0,
                                                            np.float16))
     assert np.array_equal(got.view(np.uint16), want.view(np.uint16))
     layer.k_pool.copy_(layer.half(k_pool))
@@ -57,7 +57,7 @@ def test_append_meta_and_kv_write_bit_exact(ragged):
     layer.k_pool.copy_(layer.half(kp))
     layer.v_pool.copy_(layer.half(vp))
     layer.set_seq_lens(lens)
-    meta = O.build_meta(kp, table, lens, meta_init=np.full((N, w.num_heads, 2, w.head_dim), 77.0,
+    meta = O.build_meta(kp, table, lens, meta_init=np.full((w.num_heads, N, 2, w.head_dim), 77.0,
                                                            np.float16))
     layer.build_meta()
     cur = lens.copy()
@@ -157,7 +157,7 @@ def test_topk_long_rows(max_pages, lens):
     lens = np.array(lens, np.int32)
     # placeholder pools: the selection kernel never touches them
     dummy = torch.zeros((1, H, S, 128), dtype=torch.float16, device=dev)
-    meta = torch.zeros((1, H, 2, 128), dtype=torch.float16, device=dev)
+    meta = torch.zeros((H, 1, 2, 128), dtype=torch.float16, device=dev)
     pt = torch.zeros((B, max_pages), dtype=torch.int32, device=dev)
     cache = Q.Cache(dummy, dummy, meta, pt, torch.from_numpy(lens).to(dev))
     scd = torch.from_numpy(sc).to(dev)
@@ -270,13 +270,13 @@ def test_offsets_beyond_4gib():
     ids = torch.from_numpy(hi_ids.astype(np.int64)).to(dev)
     k_pool[ids] = torch.from_numpy(k_s.view(np.int16)).to(dev).view(torch.float16)
     v_pool[ids] = torch.from_numpy(v_s.view(np.int16)).to(dev).view(torch.float16)
-    meta = torch.zeros((N, H, 2, D), dtype=torch.float16, device=dev)
+    meta = torch.zeros((H, N, 2, D), dtype=torch.float16, device=dev)
     pt = torch.from_numpy(table).to(dev)
     sl = torch.from_numpy(lens).to(dev)
     cache = Q.Cache(k_pool, v_pool, meta, pt, sl)
     Q.quest_build_meta(cache)
     want_meta = O.build_meta(k_s, small_table, lens)
-    got_meta = meta[ids].view(torch.int16).cpu().numpy().view(np.float16)
+    got_meta = meta[:, ids].contiguous().view(torch.int16).cpu().numpy().view(np.float16)
     assert np.array_equal(got_meta.view(np.uint16), want_meta.view(np.uint16))
     scores = torch.zeros((1, H, table.shape[1]), dtype=torch.float32, device=dev)
     qd = torch.from_numpy(q.view(np.int16)).to(dev).view(torch.float16)

@@ -79,8 +79,8 @@ def test_build_meta_equals_exhaustive_scan(seed):
             for h in range(H):
                 toks = [[int(bits[phys, h, s, i]) for i in range(D)] for s in range(n)]
                 mn, mx = brute_meta_entry(toks)
-                assert [int(x) for x in mbits[phys, h, 0]] == mn
-                assert [int(x) for x in mbits[phys, h, 1]] == mx
+                assert [int(x) for x in mbits[h, phys, 0]] == mn
+                assert [int(x) for x in mbits[h, phys, 1]] == mx
 
 
 def test_meta_signed_zero_order():
@@ -100,7 +100,7 @@ def test_meta_signed_zero_order():
 def test_meta_bounds_every_token_and_ignores_unmapped():
     k_pool, _, _, table, lens = small_case(7)
     N, H, S, D = k_pool.shape
-    init = np.full((N, H, 2, D), 123.0, np.float16)
+    init = np.full((H, N, 2, D), 123.0, np.float16)
     meta = O.build_meta(k_pool, table, lens, meta_init=init)
     mapped = set()
     for b, L in enumerate(lens):
@@ -109,10 +109,10 @@ def test_meta_bounds_every_token_and_ignores_unmapped():
             phys = table[b, p]
             mapped.add(int(phys))
             kk = k_pool[phys, :, :n, :].astype(np.float64)
-            assert (meta[phys, :, 0, None, :].astype(np.float64) <= kk).all()
-            assert (meta[phys, :, 1, None, :].astype(np.float64) >= kk).all()
+            assert (meta[:, phys, 0, None, :].astype(np.float64) <= kk).all()
+            assert (meta[:, phys, 1, None, :].astype(np.float64) >= kk).all()
     for phys in set(range(N)) - mapped:
-        assert (meta[phys] == np.float16(123.0)).all()
+        assert (meta[:, phys] == np.float16(123.0)).all()
 
 
 def test_incremental_update_equals_bulk_build():
@@ -124,7 +124,7 @@ def test_incremental_update_equals_bulk_build():
     table = np.array([[4, 0, 2], [1, 5, 3]], np.int32)
     k_pool = np.full((6, H, S, D), np.nan, np.float16)
     v_pool = np.full((6, H, S, D), np.nan, np.float16)
-    meta = np.full((6, H, 2, D), np.nan, np.float16)
+    meta = np.full((H, 6, 2, D), np.nan, np.float16)
     lens = np.zeros(B, np.int32)
     for t in range(max(final)):
         active = [b for b in range(B) if t < final[b]]
@@ -153,8 +153,8 @@ def test_meta_invariant_under_physical_permutation():
     meta2 = O.build_meta(k2, table2, lens)
     for b, L in enumerate(lens):
         for p in range(O.num_pages(L, S)):
-            assert np.array_equal(meta[table[b, p]].view(np.uint16),
-                                  meta2[table2[b, p]].view(np.uint16))
+            assert np.array_equal(meta[:, table[b, p]].view(np.uint16),
+                                  meta2[:, table2[b, p]].view(np.uint16))
 
 
 # ------------------------------------------------------------------ estimate
@@ -218,8 +218,8 @@ def test_score_sign_definite_queries_and_closed_form():
     k_pool, _, q, table, lens = small_case(4)
     S = k_pool.shape[2]
     meta = O.build_meta(k_pool, table, lens)
-    m = meta[:, :, 0].astype(np.float64)
-    M = meta[:, :, 1].astype(np.float64)
+    m = meta[:, :, 0].astype(np.float64).transpose(1, 0, 2)     # -> [N][H][D]
+    M = meta[:, :, 1].astype(np.float64).transpose(1, 0, 2)
     qa = np.abs(q)
     sp = O.estimate(meta, qa, table, lens, S)
     sn = O.estimate(meta, -qa, table, lens, S)
