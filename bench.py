@@ -94,6 +94,8 @@ def main():
         Q.quest_build_meta(Q.Cache(kp, vp, meta, pt, lens0_dev))
         layers.append((kp, vp, meta))
     caches = [Q.Cache(*layers[i % n_layers], pt, lens_dev[i]) for i in range(n_total)]
+    caches_persistent = [Q.Cache(*layers[i % n_layers], pt, lens_dev[i],
+                                 flags=Q.QUEST_FLAG_PERSISTENT_STEP) for i in range(n_total)]
     scores = torch.zeros((B, H, table.shape[1]), dtype=torch.float32, device=dev)
     idx = torch.zeros((B, H, K), dtype=torch.int32, device=dev)
     out = torch.zeros((B, H, D), dtype=torch.float32, device=dev)
@@ -119,8 +121,8 @@ def main():
         Q.quest_sparse_decode(c, q_all[i], idx, K, scale, out, None, ws)
 
     def single_launch_step(i):                            # the whole step in one launch
-        Q.quest_decode_step(caches[i], kn_all[i], vn_all[i], True, q_all[i], K, scale, scores, idx,
-                            out, ws_step)
+        Q.quest_decode_step(caches_persistent[i], kn_all[i], vn_all[i], True, q_all[i], K, scale,
+                            scores, idx, out, ws_step)
 
     def dense_step(i):
         c = caches[i]

@@ -64,6 +64,16 @@ typedef enum quest_status {
   QUEST_ERR_HIP = -5          /* the HIP runtime refused the launch          */
 } quest_status;
 
+/* quest_cache.flags.  Neither flag changes any result.
+ *  QUEST_FLAG_PERSISTENT_STEP: quest_decode_step runs the whole step as one
+ *    persistent launch (per-die task queues) instead of three launches; it is
+ *    slower than the three launches at the sizes measured so far and is kept
+ *    selectable for tuning.
+ *  QUEST_FLAG_DEVICE_FENCES: work-groups that exchange partial results inside a
+ *    launch always use device-scope release/acquire fences, as they do on their
+ *    own when they find themselves on different dies (for testing that path). */
+enum { QUEST_FLAG_PERSISTENT_STEP = 1, QUEST_FLAG_DEVICE_FENCES = 2 };
+
 /* Description of one layer's paged KV cache.  Host struct, passed by pointer;
  * the library reads it during the call only. */
 typedef struct quest_cache {
@@ -72,7 +82,7 @@ typedef struct quest_cache {
   int32_t head_dim;           /* D, must be 128                              */
   int32_t page_size;          /* S, must be 16                               */
   int32_t max_pages_per_seq;  /* row stride of page_table and of scores      */
-  int32_t reserved;           /* set to 0                                    */
+  int32_t flags;              /* QUEST_FLAG_* bits, normally 0               */
   int64_t num_phys_pages;     /* capacity of the pools, in pages             */
   void* k_pool;               /* device, fp16                                */
   void* v_pool;               /* device, fp16                                */
@@ -151,7 +161,7 @@ int quest_sparse_decode(const quest_cache* cache, const void* q, const int32_t* 
                         int32_t k_pages, float sm_scale, void* out, int32_t out_is_fp16,
                         float* lse, void* workspace, size_t workspace_bytes, void* stream);
 
-/* The whole decode step of one layer in a single launch (Algorithm 1 and
+/* The whole decode step of one layer in one call (Algorithm 1 and
  * Figure 5): quest_append_estimate (quest_estimate if k_new == NULL), then
  * quest_topk, then quest_sparse_decode with the list just selected.  k_pool /
  * v_pool / meta / scores / topk_idx / k_eff receive exactly what those calls
@@ -166,8 +176,9 @@ int quest_sparse_decode(const quest_cache* cache, const void* q, const int32_t* 
  * workspace is a sticky status: 0 = every launch so far completed all its work;
  * non-zero = a launch left work undone (a compute die received no work-group,
  * or an internal bounded wait expired) and its outputs must not be used.
- * On devices other than the 256-CU MI355X, or for max_pages_per_seq > 8192,
- * the call runs the three launches named above instead. */
+ * By default the call enqueues the three launches named above (one host call
+ * instead of three); with QUEST_FLAG_PERSISTENT_STEP, on the 256-CU MI355X and
+ * for max_pages_per_seq <= 8192, it is a single persistent launch. */
 int quest_step_workspace_bytes(const quest_cache* cache, int32_t k_pages, size_t* out_bytes);
 int quest_decode_step(const quest_cache* cache, const void* k_new, const void* v_new,
                       int32_t k_pool_write, const void* q, int32_t k_pages, float sm_scale,

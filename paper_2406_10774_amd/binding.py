@@ -14,6 +14,8 @@ _PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG_DIR, "libquest.so")
 
 QUEST_OK = 0
+QUEST_FLAG_PERSISTENT_STEP = 1
+QUEST_FLAG_DEVICE_FENCES = 2
 STATUS_NAMES = {0: "QUEST_OK", -1: "QUEST_ERR_NULL", -2: "QUEST_ERR_SHAPE",
                 -3: "QUEST_ERR_UNSUPPORTED", -4: "QUEST_ERR_WORKSPACE", -5: "QUEST_ERR_HIP"}
 
@@ -32,7 +34,7 @@ class quest_cache(ctypes.Structure):
     _fields_ = [
         ("batch", ctypes.c_int32), ("num_heads", ctypes.c_int32),
         ("head_dim", ctypes.c_int32), ("page_size", ctypes.c_int32),
-        ("max_pages_per_seq", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("max_pages_per_seq", ctypes.c_int32), ("flags", ctypes.c_int32),
         ("num_phys_pages", ctypes.c_int64),
         ("k_pool", ctypes.c_void_p), ("v_pool", ctypes.c_void_p), ("meta", ctypes.c_void_p),
         ("page_table", ctypes.c_void_p), ("seq_lens", ctypes.c_void_p),
@@ -93,13 +95,13 @@ class Cache:
 
     Holds references to the caller's torch tensors so they outlive the calls."""
 
-    def __init__(self, k_pool, v_pool, meta, page_table, seq_lens):
+    def __init__(self, k_pool, v_pool, meta, page_table, seq_lens, flags=0):
         N, H, S, D = k_pool.shape
         self.k_pool, self.v_pool, self.meta = k_pool, v_pool, meta
         self.page_table, self.seq_lens = page_table, seq_lens
         self.c = quest_cache(
             batch=page_table.shape[0], num_heads=H, head_dim=D, page_size=S,
-            max_pages_per_seq=page_table.shape[1], reserved=0, num_phys_pages=N,
+            max_pages_per_seq=page_table.shape[1], flags=int(flags), num_phys_pages=N,
             k_pool=k_pool.data_ptr(), v_pool=v_pool.data_ptr() if v_pool is not None else None,
             meta=meta.data_ptr(), page_table=page_table.data_ptr(), seq_lens=seq_lens.data_ptr())
 
@@ -161,3 +163,4 @@ def quest_decode_step(cache: Cache, k_new, v_new, k_pool_write, q, k_pages, sm_s
         cache.ref, _ptr(k_new), _ptr(v_new), int(bool(k_pool_write)), _ptr(q), int(k_pages),
         float(sm_scale), _ptr(scores), _ptr(topk_idx), _ptr(k_eff), _ptr(out),
         int(out.dtype == torch.float16), _ptr(lse), _ptr(workspace), ws_bytes, _stream(stream)))
+

@@ -147,6 +147,10 @@ __global__ __launch_bounds__(kDecThreads) void decode_split_kernel(const DecodeA
 
   // the four DPP rows of the wave, then the four waves of the group
   DEC_TRACE(2);
+  // every member checked in when it started, microseconds ago: read the team word
+  // now, the answer is needed only when this split publishes
+  uint64_t seen = 0;
+  if (a.splits > 1 && threadIdx.x == 0) seen = team_load(team_word);
   merge_lanes(st, 16);
   merge_lanes(st, 32);
   if (lane < 16) {
@@ -188,7 +192,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_split_kernel(const DecodeA
   wait_stores();
   __syncthreads();
   if (t == 0) {
-    const uint64_t before = team_publish(team_word, a.splits, die, a.force_device_fences);
+    const uint64_t before = team_publish(team_word, seen, a.splits, die, a.force_device_fences);
     sm_before[0] = (uint32_t)before;
     sm_before[1] = (uint32_t)(before >> 32);
   }
@@ -299,7 +303,7 @@ int launch_sparse_decode(const quest_cache& c, const void* q, const int32_t* top
   a.splits = p.splits;
   a.list_len = p.list_len;
   a.per_split = p.per_split;
-  a.force_device_fences = force_fences;
+  a.force_device_fences = force_fences || (c.flags & QUEST_FLAG_DEVICE_FENCES) != 0;
   a.out = out;
   a.out_is_fp16 = out_is_fp16;
   a.lse = lse;

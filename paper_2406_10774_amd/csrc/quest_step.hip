@@ -365,12 +365,12 @@ StepPlan plan_step(const quest_cache& c, int k_pages) {
       cus = -1;
     (void)hipGetLastError();
   }
-  static const int disable = env_int("QUEST_STEP_UNFUSED", 0);
   StepPlan p;
-  // The die-queue scheme is laid out for the full MI355X: 8 dies x 32 CUs.  Any
-  // other device shape, or rows too long for the in-register selection, takes
-  // the three-launch path.
-  p.fused = !disable && cus == 256 && c.max_pages_per_seq <= kStepThreads * 16;
+  // The persistent kernel is opt-in, and its die-queue scheme is laid out for the
+  // full MI355X (8 dies x 32 CUs); any other device shape, or rows too long for
+  // the in-register selection, takes the three-launch path.
+  p.fused = (c.flags & QUEST_FLAG_PERSISTENT_STEP) && cus == 256 &&
+            c.max_pages_per_seq <= kStepThreads * 16;
   p.groups = 2 * 256;
   // Estimate tasks of 64 pages: with the queue in item order, the work-groups of
   // a die first all work on its first items and then on the rest, so the

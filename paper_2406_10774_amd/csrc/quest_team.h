@@ -69,12 +69,15 @@ __device__ __forceinline__ uint64_t team_load(const uint64_t* word) {
 
 // Publish: to be called by ONE thread after every wave of the work-group has
 // waited for its own result stores (s_waitcnt vmcnt(0)) and the work-group has
-// passed a barrier.  Writes back this die's L2 first unless the whole team is
-// known to share the die.  Returns the word as it was before this member's
-// ticket: the member is the last one iff its ticket field equals n - 1.
-__device__ __forceinline__ uint64_t team_publish(uint64_t* word, uint32_t n, uint32_t die,
-                                                 bool force_fences) {
-  const uint64_t seen = team_load(word);
+// passed a barrier.  `seen` is the team word as loaded (team_load) by the same
+// thread any time after the launch's check-ins can have landed -- typically
+// issued together with the result stores so that its latency hides behind
+// theirs; it only decides whether this die's L2 has to be written back first
+// (unless the whole team is known to share the die).  Returns the word as it was
+// before this member's ticket: the member is the last one iff its ticket field
+// equals n - 1.
+__device__ __forceinline__ uint64_t team_publish(uint64_t* word, uint64_t seen, uint32_t n,
+                                                 uint32_t die, bool force_fences) {
   if (force_fences || !team_on_one_die(seen, n, die))
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
   return __hip_atomic_fetch_add(word, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -59,6 +59,17 @@ __device__ __forceinline__ BinHit find_bin(const uint32_t* hist, int need, int l
   return r;
 }
 
+#ifdef QUEST_STEP_TRACE
+#define TOPK_TRACE(slot)                                                        \
+  do {                                                                          \
+    if (threadIdx.x == 0 && trace) trace[(slot)] = wall_clock64();              \
+  } while (0)
+#else
+#define TOPK_TRACE(slot) \
+  do {                   \
+  } while (0)
+#endif
+
 template <int kThreads>
 struct TopkShared {
   uint32_t hist[4][256];
@@ -73,8 +84,10 @@ template <int kThreads, int kItems, bool kL2Loads>
 __device__ __forceinline__ void topk_block(TopkShared<kThreads>& sm, const float* __restrict__ row,
                                            const int32_t* __restrict__ seq_len_ptr, int max_pages,
                                            int k_pages, int32_t* __restrict__ out,
-                                           int32_t* __restrict__ k_eff_slot) {
+                                           int32_t* __restrict__ k_eff_slot,
+                                           unsigned long long* trace = nullptr) {
   constexpr int kWaves = kThreads / kWave;
+  (void)trace;
   uint32_t(&hist)[4][256] = sm.hist;
   int(&wave_tot)[kWaves] = sm.wave_tot;
   uint32_t& vote = sm.vote;
@@ -88,8 +101,11 @@ __device__ __forceinline__ void topk_block(TopkShared<kThreads>& sm, const float
   const int base = tid * kItems;
   float raw[kItems];
 #pragma unroll
-  for (int j = 0; j < kItems; ++j)
-    raw[j] = base + j < max_pages ? (kL2Loads ? team_ld(row + base + j) : row[base + j]) : 0.f;
+  for (int j = 0; j < kItems; ++j) {
+    // clamped, not predicated: the loads stay independent and all in flight at once
+    const int i = min(base + j, max_pages - 1);
+    raw[j] = kL2Loads ? team_ld(row + i) : row[i];
+  }
   const float raw0 = kL2Loads ? team_ld(row) : row[0];
   const int seq_len = *seq_len_ptr;
 
@@ -105,6 +121,7 @@ __device__ __forceinline__ void topk_block(TopkShared<kThreads>& sm, const float
     return;
   }
 
+  TOPK_TRACE(4);
   uint32_t key[kItems];
   bool valid[kItems];
   const uint32_t ref_top = score_key(raw0) & 0xff000000u;
@@ -117,7 +134,8 @@ __device__ __forceinline__ void topk_block(TopkShared<kThreads>& sm, const float
   }
   if (__ballot(differs) != 0 && lane == 0) vote = 1;
   __syncthreads();
-  const bool skip_first = __builtin_amdgcn_readfirstlane(vote) == 0;  // uniform: barriers follow
+  const bool skip_first = __builtin_amdgcn_readfirstlane(vote) == 0;
+  TOPK_TRACE(5);  // uniform: barriers follow
 
   // ---- radix select.  Invariant: the selection is every key whose bits above
   // `shift + 8` ... are greater than `prefix`'s, plus `need` of the keys that
@@ -157,6 +175,7 @@ __device__ __forceinline__ void topk_block(TopkShared<kThreads>& sm, const float
     if (need == hit.count) break;  // the whole bin is selected: no need to split it further
   }
 
+  TOPK_TRACE(6);
   // ---- emit in page order.  key > bin: selected; key in bin: the first `need`.
   const uint32_t T = prefix >> decided_shift;  // decided_shift <= 24
   int n_gt = 0, n_eq = 0;

@@ -10,7 +10,8 @@ from paper_2406_10774_amd import binding as Q
 class Layer:
     """Device copy of one layer's paged KV cache plus the buffers of a decode step."""
 
-    def __init__(self, k_pool, v_pool, page_table, seq_lens, meta_fill=None, device="cuda:0"):
+    def __init__(self, k_pool, v_pool, page_table, seq_lens, meta_fill=None, device="cuda:0",
+                 flags=0):
         import torch
         self.torch = torch
         self.dev = device
@@ -24,7 +25,8 @@ class Layer:
             self.meta.fill_(meta_fill)
         self.page_table = torch.from_numpy(np.ascontiguousarray(page_table)).to(device)
         self.seq_lens = torch.from_numpy(np.asarray(seq_lens, np.int32)).to(device)
-        self.cache = Q.Cache(self.k_pool, self.v_pool, self.meta, self.page_table, self.seq_lens)
+        self.cache = Q.Cache(self.k_pool, self.v_pool, self.meta, self.page_table, self.seq_lens,
+                             flags=flags)
         self.scores = torch.full((self.B, H, self.max_pages), float("nan"), dtype=torch.float32,
                                  device=device)
 
@@ -103,7 +105,7 @@ class Layer:
         torch.cuda.synchronize()
         status = int(self._step_ws[1].item())
         assert status == 0, f"decode step left work undone (status {status})"
-        assert int(self._step_ws[0].item()) == 0          # counters re-armed
+        assert int(self._step_ws[:16].abs().max().item()) == 0   # counters re-armed
         return (self.scores.cpu().numpy(), idx.cpu().numpy(), keff.cpu().numpy(),
                 out.cpu().numpy(), lse.cpu().numpy())
 

@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol(repo_root):
 
 def make_cache(**kw):
     base = dict(batch=1, num_heads=32, head_dim=128, page_size=16, max_pages_per_seq=2048,
-                reserved=0, num_phys_pages=2048, k_pool=0x1000, v_pool=0x1000, meta=0x1000,
+                flags=0, num_phys_pages=2048, k_pool=0x1000, v_pool=0x1000, meta=0x1000,
                 page_table=0x1000, seq_lens=0x1000)
     base.update(kw)
     return binding.quest_cache(**base)

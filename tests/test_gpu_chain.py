@@ -97,7 +97,7 @@ def test_config1_full_size_chain_shuffled_pages():
     run_chain(synth.workload(1), steps=18, permute=True)   # step 17 opens nothing new, 1..16 fill page 2048
 
 
-def run_single_launch_steps(w, steps, permute):
+def run_single_launch_steps(w, steps, permute, flags):
     """quest_decode_step against the separate calls (bit-equal metadata, pools, scores
     and page list) and against the oracle (attention within tolerance)."""
     from gpu_util import Layer
@@ -105,7 +105,7 @@ def run_single_launch_steps(w, steps, permute):
     table, N = synth.make_page_table(w, permute=permute)
     k_pool, v_pool, _ = synth.fill_pools(w, table, N)
     lens = np.array(w.seq_lens, np.int32)
-    one = Layer(k_pool, v_pool, table, lens)            # single launch
+    one = Layer(k_pool, v_pool, table, lens, flags=flags)   # one call
     ref = Layer(k_pool, v_pool, table, lens)            # separate calls
     one.build_meta()
     ref.build_meta()
@@ -137,15 +137,21 @@ def run_single_launch_steps(w, steps, permute):
     assert np.array_equal(one.np16(one.v_pool).view(np.uint16), ref.np16(ref.v_pool).view(np.uint16))
 
 
-def test_single_launch_step_config0():
-    run_single_launch_steps(synth.workload(0), steps=6, permute=True)
+STEP_FLAGS = [0, 1, 2]      # three launches / persistent launch / three launches with device fences
 
 
-def test_single_launch_step_ragged_batch():
+@pytest.mark.parametrize("flags", STEP_FLAGS)
+def test_decode_step_config0(flags):
+    run_single_launch_steps(synth.workload(0), steps=6, permute=True, flags=flags)
+
+
+@pytest.mark.parametrize("flags", STEP_FLAGS)
+def test_decode_step_ragged_batch(flags):
     w = synth.Workload(92, "ragged-step", 5, 3, (1, 16 * 3 + 7, 16 * 203 + 5, 16 * 64, 16 * 130 + 15),
                        token_budget=16 * 24, planted_per_head=4, decode_steps=24)
-    run_single_launch_steps(w, steps=20, permute=True)
+    run_single_launch_steps(w, steps=20, permute=True, flags=flags)
 
 
-def test_single_launch_step_config1_full_size():
-    run_single_launch_steps(synth.workload(1), steps=4, permute=False)
+@pytest.mark.parametrize("flags", [0, 1])
+def test_decode_step_config1_full_size(flags):
+    run_single_launch_steps(synth.workload(1), steps=4, permute=False, flags=flags)
