@@ -178,7 +178,8 @@ def main():
     g_one.replay()
     one_us = time_graph(g_one, max(3, args.repeats // 2))[0] / args.steps * 1e6
     torch.cuda.synchronize()
-    assert int(ws_step[1].item()) == 0, "quest_decode_step reported unfinished work"
+    status_at = (Q.quest_step_workspace_bytes(caches[0], K) - 256) // 4
+    assert int(ws_step[status_at].item()) == 0, "quest_decode_step reported unfinished work"
 
     g_dense = capture(dense_step, timed)
     g_dense.replay()

@@ -169,16 +169,17 @@ int quest_sparse_decode(const quest_cache* cache, const void* q, const int32_t* 
  * accumulated over a different split of the page list (so equal within fp32
  * rounding, not bit for bit).  scores and topk_idx are outputs and also the
  * buffers the phases hand to each other, so they must be provided.
- * workspace: at least quest_step_workspace_bytes(cache, k_pages) bytes,
+ * workspace: at least n = quest_step_workspace_bytes(cache, k_pages) bytes,
  * zero-filled once after allocation (same rule as for quest_sparse_decode;
  * one buffer of max(both sizes) may serve both calls); calls sharing a
- * workspace must not overlap in time.  The 32-bit word at byte offset 4 of the
- * workspace is a sticky status: 0 = every launch so far completed all its work;
- * non-zero = a launch left work undone (a compute die received no work-group,
- * or an internal bounded wait expired) and its outputs must not be used.
+ * workspace must not overlap in time.  The 32-bit word at byte offset n - 256
+ * is a sticky status: 0 = every launch so far completed all its work; non-zero
+ * = an internal bounded wait of the persistent launch expired and the outputs
+ * of that launch must not be used.
  * By default the call enqueues the three launches named above (one host call
- * instead of three); with QUEST_FLAG_PERSISTENT_STEP, on the 256-CU MI355X and
- * for max_pages_per_seq <= 8192, it is a single persistent launch. */
+ * instead of three); with QUEST_FLAG_PERSISTENT_STEP, when every (sequence,
+ * head) can have its team of work-groups resident at once and
+ * max_pages_per_seq <= 8192, it is a single launch. */
 int quest_step_workspace_bytes(const quest_cache* cache, int32_t k_pages, size_t* out_bytes);
 int quest_decode_step(const quest_cache* cache, const void* k_new, const void* v_new,
                       int32_t k_pool_write, const void* q, int32_t k_pages, float sm_scale,

@@ -208,7 +208,7 @@ int quest_decode_step(const quest_cache* cache, const void* k_new, const void* v
     return QUEST_ERR_WORKSPACE;
   }
   return launch_decode_step(*cache, k_new, v_new, k_pool_write != 0, q, k_pages, sm_scale, scores,
-                            topk_idx, k_eff, out, out_is_fp16 != 0, lse, workspace,
+                            topk_idx, k_eff, out, out_is_fp16 != 0, lse, workspace, workspace_bytes,
                             (hipStream_t)stream);
 }
 

@@ -49,7 +49,7 @@ size_t step_workspace_bytes(const quest_cache& c, int k_pages);
 int launch_decode_step(const quest_cache& c, const void* k_new, const void* v_new, int k_pool_write,
                        const void* q, int k_pages, float sm_scale, float* scores, int32_t* topk_idx,
                        int32_t* k_eff, void* out, int out_is_fp16, float* lse, void* workspace,
-                       hipStream_t s);
+                       size_t workspace_bytes, hipStream_t s);
 
 // -------------------------------------------------------------- device side
 #if defined(__HIPCC__)

@@ -1,37 +1,27 @@
 // One decode step of Quest in a single launch: insertion of the new token,
 // criticality estimate, Top-K selection and sparse attention (Algorithm 1 and
-// Figure 5 of arXiv 2406.10774) chained inside one persistent kernel instead of
-// three or four launches.  Same arithmetic as the stand-alone kernels (the
-// device cores are shared), so metadata, scores and the page list are bit-equal
-// to theirs.
+// Figure 5 of arXiv 2406.10774) chained inside one kernel instead of three
+// launches.  Same arithmetic as the stand-alone kernels (the device cores are
+// shared), so metadata, scores and the page list are bit-equal to theirs.
 //
 // Why: at 32 heads / 32k context each streaming phase moves 32 MiB, about 4 us
 // at HBM speed, while a kernel boundary costs 1.6 us plus the drain and ramp of
-// the machine, and the dependent phases of different heads cannot overlap across
-// launches.  Here the phases of a head are chained by per-head counters.
+// the machine.
 //
-// Scheme.  A (sequence, head) pair is an "item"; item i belongs to die i % 8.
-// Each die has a queue (one ticket counter) of tasks in a fixed order: first
-// every estimate task of its items (64 or 128 pages each), then
-// every attention task (a slice of the selected-page list).  Work-groups are
-// persistent: a work-group reads the id of the die it really runs on and
-// serves that die's queue until it is empty.  Everything the work-groups of an
-// item hand to each other (scores, page list, split partials) therefore stays
-// inside one die, whose L2 is coherent: plain stores, a wait for the stores, an
-// L2 atomic, device-scope loads -- no device-wide cache maintenance.
-//   * the work-group that finishes the last estimate task of an item runs the
-//     Top-K selection for it and then raises the item's "list ready" flag;
-//   * an attention task first waits for that flag;
-//   * the work-group that finishes the last attention task of an item merges
-//     the item's split partials and writes the output.
-// No deadlock by construction: a work-group only ever waits (for the flag)
-// while holding an attention task, and a queue hands out attention tasks only
-// after all its estimate tasks have been handed out to work-groups that are
-// running and never wait; so the flag is always on its way.  The wait is
-// bounded anyway and raises a status word instead of hanging.
-// The last work-group to leave checks that every queue was served (a die that
-// got no work-group at all would leave its items undone: status word) and
-// re-arms all counters for the next launch.
+// Scheme.  Every (sequence, head) has a team of M work-groups (8 waves each),
+// laid out on one die (quest_team.h).  Member m
+//   1. scores its slice of the head's pages (and inserts the new token if it
+//      falls into the slice), publishes; the member that arrives last selects
+//      the head's pages and raises the head's "list ready" flag;
+//   2. waits for the flag, runs attention over its slice of the selected-page
+//      list, publishes its partial; the member that arrives last merges, writes
+//      the output and re-arms the head's counters for the next launch.
+// A member only waits after finishing its own estimate, and the flag is raised
+// by whichever member finishes its estimate last, so the wait cannot deadlock as
+// long as the members of a team get to run; the host keeps the grid within what
+// is resident at once, and the wait is bounded anyway (status word instead of a
+// hang).  Exchanges between members go through the die's L2 when the whole team
+// is known to share a die, through device-scope fences otherwise.
 #include "quest_common.h"
 #include "quest_decode_core.h"
 #include "quest_estimate_core.h"
@@ -45,15 +35,11 @@ namespace quest {
 namespace {
 
 constexpr int kStepThreads = 512;
-constexpr int kStepWaves = kStepThreads / kWave;              // 8
-constexpr int kNumDies = 8;
-constexpr int kSlotWords = 64;  // 256-byte slots of uint32 words
-// workspace words: slot 0 = {leavers, status}; slots 1..8 = die queues;
-// slots 9.. = one per item {estimate tasks done, list ready, attention tasks done}
-constexpr int kItemSlot0 = 1 + kNumDies;
+constexpr int kStepWaves = kStepThreads / kWave;  // 8
+constexpr int kSlotBytes = 256;                   // per (sequence, head): team word, flag, arrivals
 constexpr uint32_t kSpinLimit = 1u << 20;  // about a second; the flag normally arrives within microseconds
 
-enum : uint32_t { kStatusDieNotServed = 1, kStatusWaitTimedOut = 2 };
+enum : uint32_t { kStatusWaitTimedOut = 2 };
 
 struct StepArgs {
   EstimateArgs est;
@@ -63,14 +49,14 @@ struct StepArgs {
   int32_t* k_eff;
   void* out;
   float* lse;
-  uint32_t* words;   // counters (see above)
-  float* part_acc;   // [items * dec_tasks][D]
-  float* part_ml;    // [items * dec_tasks][2]
-  int batch, k_pages, out_is_fp16;
-  int est_iters;     // pages per DPP row in an estimate task (2 or 4): a task covers 32 * est_iters pages
-  int est_tasks;     // E: estimate tasks per item = ceil(max_pages / (32 * est_iters))
-  int dec_tasks;     // Dn: attention tasks per item
-  int pages_per_wave;  // list positions per wave in an attention task (<= 64)
+  char* slots;        // [items] 256-byte slots: u64 team word, u32 list-ready flag, u32 attention arrivals
+  uint32_t* status;   // sticky: non-zero = a launch left work undone
+  float* part_acc;    // [items * members][D]
+  float* part_ml;     // [items * members][2]
+  int batch, k_pages, out_is_fp16, force_device_fences;
+  int members;        // M: work-groups per (sequence, head)
+  int est_calls;      // blocks of 32 * kIters pages a member scores one after the other
+  int list_per_member;  // selected-list positions per member
   float scale_log2;
 #ifdef QUEST_STEP_TRACE
   unsigned long long* trace;
@@ -88,10 +74,9 @@ __device__ __forceinline__ void word_set(uint32_t* p, uint32_t v) {
 }
 
 #ifdef QUEST_STEP_TRACE
-#define STEP_TRACE(slot)                                                              \
-  do {                                                                                \
-    if (threadIdx.x == 0 && a.trace && a.trace[(size_t)blockIdx.x * 16 + (slot)] == 0) \
-      a.trace[(size_t)blockIdx.x * 16 + (slot)] = wall_clock64();                     \
+#define STEP_TRACE(slot)                                                                  \
+  do {                                                                                    \
+    if (threadIdx.x == 0 && a.trace) a.trace[(size_t)blockIdx.x * 16 + (slot)] = wall_clock64(); \
   } while (0)
 #else
 #define STEP_TRACE(slot) \
@@ -106,34 +91,111 @@ struct StepShared {
   uint32_t u[4];
 };
 
-// ---- attention task: slice `chunk` of the item's page list
-__device__ __forceinline__ void attention_task(const StepArgs& a, StepShared& sm, int item, int chunk,
-                                               uint32_t* state) {
+// In every barrier-separated section below, values read from LDS that steer
+// control flow go through readfirstlane and every single-lane section is closed
+// by a barrier: otherwise the compiler may let part of wave 0 run ahead to the
+// next s_barrier alone (the hardware barrier counts waves, not lanes).
+template <int kItems, int kIters, bool kAppend>
+__global__ __launch_bounds__(kStepThreads, 4) void step_kernel(const StepArgs a) {
+  __shared__ StepShared sm;
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = lane_id();
   const int grp = lane >> 4;
   const int c = lane & 15;
   const int num_heads = a.est.num_heads, max_pages = a.est.max_pages;
+  const int M = a.members;
+
+  const int slot = blockIdx.x & 7;
+  const int rank = blockIdx.x >> 3;
+  const int member = rank % M;
+  const int item = (rank / M) * 8 + slot;
+  if (item >= a.batch * num_heads) return;
   const int b = item / num_heads;
   const int h = item - b * num_heads;
+  const uint32_t die = xcc_id();
+  char* st_slot = a.slots + (size_t)item * kSlotBytes;
+  uint64_t* team_word = reinterpret_cast<uint64_t*>(st_slot);
+  uint32_t* flag = reinterpret_cast<uint32_t*>(st_slot + 8);
+  uint32_t* arrivals = reinterpret_cast<uint32_t*>(st_slot + 12);
+  if (M > 1 && tid == 0) team_checkin(team_word, die);
+  STEP_TRACE(0);
 
-  // the page list must be complete
-  if (tid == 0) {
-    uint32_t spins = 0;
-    while (word_load(state + 1) == 0u) {
-      __builtin_amdgcn_s_sleep(1);
-      if (++spins > kSpinLimit) {
-        word_set(a.words + 1, kStatusWaitTimedOut);
-        break;
+  // ---- 1. estimate (and insertion) over this member's slice of the pages
+  {
+    constexpr int kWavePages = 4 * kIters;
+    const int span = kStepWaves * kWavePages * a.est_calls;
+    for (int call = 0; call < a.est_calls; ++call)
+      estimate_wave<kAppend, kIters>(a.est, b, h,
+                                     member * span + (call * kStepWaves + wave) * kWavePages);
+  }
+  uint64_t seen = 0;
+  if (M > 1 && tid == 0) seen = team_load(team_word);
+  wait_stores();
+  STEP_TRACE(1);
+  __syncthreads();
+  bool fenced = false, last_est = true;
+  if (M > 1) {
+    if (tid == 0) {
+      const uint64_t before = team_publish(team_word, seen, M, die, a.force_device_fences);
+      sm.u[0] = (uint32_t)before;
+      sm.u[1] = (uint32_t)(before >> 32);
+    }
+    __syncthreads();
+    const uint64_t before = (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane(sm.u[0]) |
+                            ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane(sm.u[1]) << 32);
+    // definitive when true: all M members have started and share this die
+    fenced = a.force_device_fences || !team_on_one_die(before, M, die);
+    last_est = team_is_last(before, M);
+    __syncthreads();
+  }
+  STEP_TRACE(2);
+#ifdef QUEST_STEP_TRACE
+  if (tid == 0 && a.trace) {
+    a.trace[(size_t)blockIdx.x * 16 + 8] = fenced ? 1 : 2;
+    a.trace[(size_t)blockIdx.x * 16 + 9] = die + 100;
+    a.trace[(size_t)blockIdx.x * 16 + 10] = ((uint64_t)sm.u[1] << 32) | sm.u[0];
+    a.trace[(size_t)blockIdx.x * 16 + 11] = seen;
+  }
+#endif
+
+  // ---- 2. the member that finished the head's estimate selects its pages
+  if (last_est) {
+    if (fenced) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    topk_block<kStepThreads, kItems, true>(
+        sm.topk, a.est.scores + (size_t)item * max_pages, a.est.seq_lens + b, max_pages, a.k_pages,
+        a.topk_idx + (size_t)item * a.k_pages, (h == 0 && a.k_eff != nullptr) ? a.k_eff + b : nullptr);
+    wait_stores();
+    __syncthreads();
+    if (M > 1 && tid == 0) {
+      if (fenced) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+      word_set(flag, 1u);
+    }
+    __syncthreads();
+    STEP_TRACE(3);
+  }
+
+  // ---- 3. attention over this member's slice of the selected-page list
+  if (M > 1) {
+    if (tid == 0) {
+      uint32_t spins = 0;
+      while (word_load(flag) == 0u) {
+        __builtin_amdgcn_s_sleep(1);
+        if (++spins > kSpinLimit) {
+          word_set(a.status, kStatusWaitTimedOut);
+          break;
+        }
       }
     }
+    __syncthreads();
+    if (fenced) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
   }
-  __syncthreads();
-  STEP_TRACE(6);
+  STEP_TRACE(4);
 
   const int list_len = a.k_pages < max_pages ? a.k_pages : max_pages;
-  const int begin = chunk * kStepWaves * a.pages_per_wave;
+  const int begin = member * a.list_per_member;
+  const int end = min(list_len, begin + a.list_per_member);
+  const int n_here = (a.list_per_member + kStepWaves - 1) / kStepWaves;  // <= 64 (host)
   const int32_t* idx_row = a.topk_idx + (size_t)item * a.k_pages;
   const int32_t* pt = a.est.page_table + (size_t)b * max_pages;
   const int seq_len = a.est.seq_lens[b];
@@ -142,7 +204,7 @@ __device__ __forceinline__ void attention_task(const StepArgs& a, StepShared& sm
   // lane i: i-th list entry of this wave (positions begin + wave + 8 i)
   const int pos = begin + wave + kStepWaves * lane;
   int lp_v = -1;
-  if (lane < a.pages_per_wave && pos < list_len) lp_v = team_ld(idx_row + pos);
+  if (lane < n_here && pos < end) lp_v = team_ld(idx_row + pos);
   int ph_v = 0;
   if (lp_v >= 0 && lp_v < max_pages) ph_v = pt[lp_v];
   const int num_pages = (seq_len + kPageSize - 1) / kPageSize;
@@ -153,9 +215,7 @@ __device__ __forceinline__ void attention_task(const StepArgs& a, StepShared& sm
   st.l = 0.f;
 #pragma unroll
   for (int j = 0; j < 8; ++j) st.acc[j] = 0.f;
-
   {
-    const int n_here = a.pages_per_wave;
     PageRegs ra, rb;
     int j = 0;
     int lp = __builtin_amdgcn_readlane(lp_v, 0);
@@ -179,8 +239,8 @@ __device__ __forceinline__ void attention_task(const StepArgs& a, StepShared& sm
       fold_page(st, rb, qv, a.scale_log2, grp);
     }
   }
+  STEP_TRACE(5);
 
-  STEP_TRACE(7);
   merge_lanes(st, 16);
   merge_lanes(st, 32);
   if (lane < 16) {
@@ -202,17 +262,16 @@ __device__ __forceinline__ void attention_task(const StepArgs& a, StepShared& sm
     l_tot += sm.l[w] * f;
     acc += sm.acc[w][tid & (kHeadDim - 1)] * f;
   }
-  if (a.dec_tasks == 1) {
+  if (M == 1) {
     if (tid < kHeadDim) {
       store_out(a.out, a.out_is_fp16, (size_t)item * kHeadDim + tid, acc / l_tot);
       if (tid == 0 && a.lse) a.lse[item] = (m_tot + __builtin_amdgcn_logf(l_tot)) * kLn2;
     }
-    __syncthreads();  // sm is reused by the next task
     return;
   }
 
-  // publish the partial; the task that arrives last merges
-  const size_t ps = (size_t)item * a.dec_tasks + chunk;
+  // publish the partial; the member that arrives last merges and re-arms
+  const size_t ps = (size_t)item * M + member;
   if (tid < kHeadDim) a.part_acc[ps * kHeadDim + tid] = acc;
   if (tid == 0) {
     a.part_ml[ps * 2 + 0] = m_tot;
@@ -220,21 +279,30 @@ __device__ __forceinline__ void attention_task(const StepArgs& a, StepShared& sm
   }
   wait_stores();
   __syncthreads();
-  if (tid == 0) sm.u[1] = word_add(state + 2, 1u);
+  if (tid == 0) {
+    if (fenced) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    sm.u[2] = word_add(arrivals, 1u);
+  }
   __syncthreads();
-  const bool last = __builtin_amdgcn_readfirstlane(sm.u[1]) == (uint32_t)a.dec_tasks - 1;
-  STEP_TRACE(8);
-  __syncthreads();
-  if (!last || tid >= kHeadDim) return;
+  const bool last = __builtin_amdgcn_readfirstlane(sm.u[2]) == (uint32_t)M - 1;
+  STEP_TRACE(6);
+  if (!last) return;
+  if (fenced) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+  if (tid == 0) {  // every member has passed all its waits: re-arm for the next launch
+    team_reset(team_word);
+    word_set(flag, 0u);
+    word_set(arrivals, 0u);
+  }
+  if (tid >= kHeadDim) return;
 
-  const float* ml = a.part_ml + (size_t)item * a.dec_tasks * 2;
-  const float* pacc = a.part_acc + (size_t)item * a.dec_tasks * kHeadDim + tid;
+  const float* ml = a.part_ml + (size_t)item * M * 2;
+  const float* pacc = a.part_acc + (size_t)item * M * kHeadDim + tid;
   float mx = kNegBig, l_all = 0.f, o = 0.f;
-  for (int s0 = 0; s0 < a.dec_tasks; s0 += 16) {
+  for (int s0 = 0; s0 < M; s0 += 16) {
     float pm[16], pl[16], pa[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const int sidx = min(s0 + i, a.dec_tasks - 1);
+      const int sidx = min(s0 + i, M - 1);
       pm[i] = team_ld(ml + 2 * sidx);
       pl[i] = team_ld(ml + 2 * sidx + 1);
       pa[i] = team_ld(pacc + (size_t)sidx * kHeadDim);
@@ -247,7 +315,7 @@ __device__ __forceinline__ void attention_task(const StepArgs& a, StepShared& sm
     o *= rescale;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const float f = s0 + i < a.dec_tasks ? __builtin_amdgcn_exp2f(pm[i] - cm) : 0.f;
+      const float f = s0 + i < M ? __builtin_amdgcn_exp2f(pm[i] - cm) : 0.f;
       l_all += pl[i] * f;
       o += pa[i] * f;
     }
@@ -255,93 +323,7 @@ __device__ __forceinline__ void attention_task(const StepArgs& a, StepShared& sm
   }
   store_out(a.out, a.out_is_fp16, (size_t)item * kHeadDim + tid, o / l_all);
   if (tid == 0 && a.lse) a.lse[item] = (mx + __builtin_amdgcn_logf(l_all)) * kLn2;
-  STEP_TRACE(9);
-}
-
-template <int kItems, bool kAppend>
-__global__ __launch_bounds__(kStepThreads, 4) void step_kernel(const StepArgs a) {
-  __shared__ StepShared sm;
-  const int tid = threadIdx.x;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int die = xcc_id() & (kNumDies - 1);
-  const int num_heads = a.est.num_heads, max_pages = a.est.max_pages;
-  const int items = a.batch * num_heads;
-  const int my_items = items > die ? (items - die + kNumDies - 1) / kNumDies : 0;
-  const uint32_t n_est = (uint32_t)my_items * a.est_tasks;
-  const uint32_t total = n_est + (uint32_t)my_items * a.dec_tasks;
-  uint32_t* queue = a.words + (1 + die) * kSlotWords;
-  STEP_TRACE(0);
-
-  for (;;) {
-    if (tid == 0) sm.u[0] = word_add(queue, 1u);
-    __syncthreads();
-    // the value is the same in every lane; say so, or the loop counts as divergent
-    // and the barriers inside it stop being reached by whole waves together
-    const uint32_t ticket = __builtin_amdgcn_readfirstlane(sm.u[0]);
-    __syncthreads();
-    if (ticket >= total) break;
-    if (ticket < n_est) {
-      STEP_TRACE(1);
-      // ---- estimate task (with the insertion of the new token where it falls)
-      const int item = (int)(ticket / a.est_tasks) * kNumDies + die;
-      const int chunk = (int)(ticket % a.est_tasks);
-      const int b = item / num_heads;
-      const int h = item - b * num_heads;
-      uint32_t* state = a.words + (size_t)(kItemSlot0 + item) * kSlotWords;
-      if (a.est_iters == 2)
-        estimate_wave<kAppend, 2>(a.est, b, h, (chunk * kStepWaves + wave) * 8);
-      else
-        estimate_wave<kAppend, 4>(a.est, b, h, (chunk * kStepWaves + wave) * 16);
-      wait_stores();
-      STEP_TRACE(2);
-      __syncthreads();
-      if (tid == 0) sm.u[1] = word_add(state, 1u);
-      __syncthreads();
-      const bool last = __builtin_amdgcn_readfirstlane(sm.u[1]) == (uint32_t)a.est_tasks - 1;
-      STEP_TRACE(3);
-      __syncthreads();
-      if (last) {
-        topk_block<kStepThreads, kItems, true>(
-            sm.topk, a.est.scores + (size_t)item * max_pages, a.est.seq_lens + b, max_pages,
-            a.k_pages, a.topk_idx + (size_t)item * a.k_pages,
-            (h == 0 && a.k_eff != nullptr) ? a.k_eff + b : nullptr);
-        wait_stores();
-        __syncthreads();
-        if (tid == 0) word_set(state + 1, 1u);
-        STEP_TRACE(4);
-        // Every single-lane section in this loop is closed by a barrier before the
-        // back-edge.  Without it the compiler may sink the section into the next
-        // iteration's single-lane ticket draw and let the other lanes of wave 0 run
-        // ahead to the next barrier alone; the hardware barrier counts waves, not
-        // lanes, so the work-group would then loop on a stale ticket for ever.
-        __syncthreads();
-      }
-    } else {
-      STEP_TRACE(5);
-      const uint32_t t = ticket - n_est;
-      const int item = (int)(t / a.dec_tasks) * kNumDies + die;
-      const int chunk = (int)(t % a.dec_tasks);
-      attention_task(a, sm, item, chunk, a.words + (size_t)(kItemSlot0 + item) * kSlotWords);
-      __syncthreads();
-    }
-  }
-
-  STEP_TRACE(10);
-  // ---- leave; the last one out checks the queues and re-arms every counter
-  if (tid == 0) sm.u[2] = word_add(a.words, 1u);
-  __syncthreads();
-  if (__builtin_amdgcn_readfirstlane(sm.u[2]) != gridDim.x - 1) return;
-  if (tid < kNumDies) {
-    const int cnt = items > tid ? (items - tid + kNumDies - 1) / kNumDies : 0;
-    const uint32_t want = (uint32_t)cnt * (a.est_tasks + a.dec_tasks);
-    uint32_t* qd = a.words + (1 + tid) * kSlotWords;
-    // a served queue ends above `want`: each of its work-groups drew one "empty" ticket
-    if (want != 0 && word_load(qd) <= want) word_set(a.words + 1, kStatusDieNotServed);
-    word_set(qd, 0u);
-  }
-  for (int i = tid; i < items * 3; i += kStepThreads)
-    word_set(a.words + (size_t)(kItemSlot0 + i / 3) * kSlotWords + i % 3, 0u);
-  if (tid == 0) word_set(a.words, 0u);
+  STEP_TRACE(7);
 }
 
 int env_int(const char* name, int fallback) {
@@ -350,72 +332,107 @@ int env_int(const char* name, int fallback) {
 }
 
 struct StepPlan {
-  int groups, est_iters, est_tasks, dec_tasks, pages_per_wave;
   bool fused;
+  int iters, est_calls, members, list_per_member;
 };
 
-StepPlan plan_step(const quest_cache& c, int k_pages) {
-  static int cus = 0;
-  if (cus == 0) {
-    int dev = 0, n = 0;
+// Work-groups of this kernel that can be resident at once on the device.
+int resident_capacity() {
+  static int cap = 0;
+  if (cap == 0) {
+    int dev = 0, cus = 0, per_cu = 0;
     if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
-      cus = n;
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(
+            &per_cu, reinterpret_cast<const void*>(&step_kernel<5, 5, true>), kStepThreads, 0) ==
+            hipSuccess)
+      cap = cus * per_cu;
     else
-      cus = -1;
+      cap = -1;
     (void)hipGetLastError();
   }
-  StepPlan p;
-  // The persistent kernel is opt-in, and its die-queue scheme is laid out for the
-  // full MI355X (8 dies x 32 CUs); any other device shape, or rows too long for
-  // the in-register selection, takes the three-launch path.
-  p.fused = (c.flags & QUEST_FLAG_PERSISTENT_STEP) && cus == 256 &&
-            c.max_pages_per_seq <= kStepThreads * 16;
-  p.groups = 2 * 256;
-  // Estimate tasks of 64 pages: with the queue in item order, the work-groups of
-  // a die first all work on its first items and then on the rest, so the
-  // selection of the first items overlaps with the estimate of the others.
-  static const int est_iters = env_int("QUEST_STEP_EST_ITERS", 2);
-  p.est_iters = est_iters == 4 ? 4 : 2;
-  const int est_pages = kStepWaves * 4 * p.est_iters;
-  p.est_tasks = (c.max_pages_per_seq + est_pages - 1) / est_pages;
+  return cap;
+}
+
+StepPlan plan_step(const quest_cache& c, int k_pages) {
+  StepPlan p = {};
   const long items = (long)c.batch * c.num_heads;
-  const long list_len = k_pages < c.max_pages_per_seq ? k_pages : c.max_pages_per_seq;
-  long ppw = (items * list_len + (long)kStepWaves * p.groups - 1) / ((long)kStepWaves * p.groups);
-  if (ppw < 1) ppw = 1;
-  if (ppw > 64) ppw = 64;
-  p.pages_per_wave = (int)ppw;
-  p.dec_tasks = (int)((list_len + kStepWaves * ppw - 1) / (kStepWaves * ppw));
+  const int cap = resident_capacity();
+  // opt-in, rows within the in-register selection, every team resident at once
+  p.fused = (c.flags & QUEST_FLAG_PERSISTENT_STEP) && cap > 0 && items <= cap &&
+            c.max_pages_per_seq <= kStepThreads * 16;
+  if (!p.fused) return p;
+  const int mp = c.max_pages_per_seq;
+  static const int force_iters = env_int("QUEST_STEP_EST_ITERS", 0);
+  const int choices[4] = {4, 5, 6, 8};
+  p.iters = 8;
+  p.est_calls = 1;
+  bool found = false;
+  for (int i = 0; i < 4 && !found; ++i) {
+    if (force_iters && choices[i] != force_iters) continue;
+    const int span = kStepWaves * 4 * choices[i];
+    const long m = (mp + span - 1) / span;
+    if (items * m <= cap) {
+      p.iters = choices[i];
+      p.members = (int)m;
+      found = true;
+    }
+  }
+  if (!found) {  // several blocks per member, 256 pages each
+    const long per_item = cap / items;  // >= 1
+    const int span1 = kStepWaves * 4 * 8;
+    p.est_calls = (int)(((mp + span1 - 1) / span1 + per_item - 1) / per_item);
+    p.members = (mp + span1 * p.est_calls - 1) / (span1 * p.est_calls);
+  }
+  if (p.members > kMaxTeamSize) {
+    p.fused = false;
+    return p;
+  }
+  const int list_len = k_pages < mp ? k_pages : mp;
+  p.list_per_member = (list_len + p.members - 1) / p.members;
+  if ((p.list_per_member + kStepWaves - 1) / kStepWaves > kWave) p.fused = false;  // one lane per entry
   return p;
 }
 
-size_t step_counter_bytes(const quest_cache& c) {
-  return (size_t)(kItemSlot0 + (size_t)c.batch * c.num_heads) * kSlotWords * sizeof(uint32_t);
+size_t slots_bytes(const quest_cache& c) { return (size_t)c.batch * c.num_heads * kSlotBytes; }
+
+template <int kItems, int kIters>
+int launch_variant(const StepArgs& a, bool append, unsigned groups, hipStream_t s) {
+  if (append)
+    hipLaunchKernelGGL((step_kernel<kItems, kIters, true>), dim3(groups), dim3(kStepThreads), 0, s, a);
+  else
+    hipLaunchKernelGGL((step_kernel<kItems, kIters, false>), dim3(groups), dim3(kStepThreads), 0, s, a);
+  return check_launch("quest_decode_step");
 }
 
 template <int kItems>
-int launch_step_items(const StepArgs& a, bool append, int groups, hipStream_t s) {
-  if (append)
-    hipLaunchKernelGGL((step_kernel<kItems, true>), dim3(groups), dim3(kStepThreads), 0, s, a);
-  else
-    hipLaunchKernelGGL((step_kernel<kItems, false>), dim3(groups), dim3(kStepThreads), 0, s, a);
-  return check_launch("quest_decode_step");
+int launch_items(const StepArgs& a, int iters, bool append, unsigned groups, hipStream_t s) {
+  switch (iters) {
+    case 4: return launch_variant<kItems, 4>(a, append, groups, s);
+    case 5: return launch_variant<kItems, 5>(a, append, groups, s);
+    case 6: return launch_variant<kItems, 6>(a, append, groups, s);
+    default: return launch_variant<kItems, 8>(a, append, groups, s);
+  }
 }
 
 }  // namespace
 
+// Layout: [items] 256-byte slots | split partials | 256-byte status slot (last).
 size_t step_workspace_bytes(const quest_cache& c, int k_pages) {
-  const StepPlan p = plan_step(c, k_pages);
-  const size_t fused = step_counter_bytes(c) + (size_t)c.batch * c.num_heads * p.dec_tasks *
-                                                   (kHeadDim + 2) * sizeof(float);
-  const size_t unfused = decode_workspace_bytes(c, k_pages);
+  // size for the largest team the plan can choose (one member per 128 pages), so
+  // that the size does not depend on flags or on the device
+  const size_t max_members = (c.max_pages_per_seq + 127) / 128;
+  const size_t fused = slots_bytes(c) +
+                       (size_t)c.batch * c.num_heads * max_members * (kHeadDim + 2) * sizeof(float) +
+                       kSlotBytes;
+  const size_t unfused = decode_workspace_bytes(c, k_pages) + kSlotBytes;
   return fused > unfused ? fused : unfused;
 }
 
 int launch_decode_step(const quest_cache& c, const void* k_new, const void* v_new, int k_pool_write,
                        const void* q, int k_pages, float sm_scale, float* scores, int32_t* topk_idx,
                        int32_t* k_eff, void* out, int out_is_fp16, float* lse, void* workspace,
-                       hipStream_t s) {
+                       size_t workspace_bytes, hipStream_t s) {
   const StepPlan p = plan_step(c, k_pages);
   if (!p.fused) {
     int r = k_new ? launch_append_estimate(c, k_new, v_new, k_pool_write, q, scores, s)
@@ -426,6 +443,7 @@ int launch_decode_step(const quest_cache& c, const void* k_new, const void* v_ne
     return launch_sparse_decode(c, q, topk_idx, k_pages, sm_scale, out, out_is_fp16, lse, workspace,
                                 s);
   }
+  static const int force_fences = env_int("QUEST_FORCE_DEVICE_FENCES", 0);
   StepArgs a;
   a.est.meta = (char*)c.meta;
   a.est.q = (const char*)q;
@@ -446,16 +464,18 @@ int launch_decode_step(const quest_cache& c, const void* k_new, const void* v_ne
   a.k_eff = k_eff;
   a.out = out;
   a.lse = lse;
-  a.words = (uint32_t*)workspace;
-  a.part_acc = (float*)((char*)workspace + step_counter_bytes(c));
-  a.part_ml = a.part_acc + (size_t)c.batch * c.num_heads * p.dec_tasks * kHeadDim;
+  a.slots = (char*)workspace;
+  (void)workspace_bytes;  // checked by the caller; the status slot sits at the end of the required size
+  a.status = (uint32_t*)((char*)workspace + step_workspace_bytes(c, k_pages) - kSlotBytes);
+  a.part_acc = (float*)((char*)workspace + slots_bytes(c));
+  a.part_ml = a.part_acc + (size_t)c.batch * c.num_heads * p.members * kHeadDim;
   a.batch = c.batch;
   a.k_pages = k_pages;
   a.out_is_fp16 = out_is_fp16;
-  a.est_iters = p.est_iters;
-  a.est_tasks = p.est_tasks;
-  a.dec_tasks = p.dec_tasks;
-  a.pages_per_wave = p.pages_per_wave;
+  a.force_device_fences = force_fences || (c.flags & QUEST_FLAG_DEVICE_FENCES) != 0;
+  a.members = p.members;
+  a.est_calls = p.est_calls;
+  a.list_per_member = p.list_per_member;
   a.scale_log2 = sm_scale * kLog2e;
 #ifdef QUEST_STEP_TRACE
   a.trace = std::getenv("QUEST_STEP_TRACE_PTR")
@@ -463,9 +483,11 @@ int launch_decode_step(const quest_cache& c, const void* k_new, const void* v_ne
                 : nullptr;
 #endif
   const bool append = k_new != nullptr;
+  const long items8 = ((long)c.batch * c.num_heads + 7) / 8 * 8;
+  const unsigned groups = (unsigned)(items8 * p.members);
   const int mp = c.max_pages_per_seq;
 #define QUEST_STEP_CASE(I) \
-  if (mp <= kStepThreads * (I)) return launch_step_items<I>(a, append, p.groups, s)
+  if (mp <= kStepThreads * (I)) return launch_items<I>(a, p.iters, append, groups, s)
   QUEST_STEP_CASE(1);
   QUEST_STEP_CASE(2);
   QUEST_STEP_CASE(3);

@@ -103,9 +103,10 @@ class Layer:
                             k_pages, sm_scale, self.scores, idx, out, self._step_ws, k_eff=keff,
                             lse=lse)
         torch.cuda.synchronize()
-        status = int(self._step_ws[1].item())
+        nbytes = Q.quest_step_workspace_bytes(self.cache, k_pages)
+        status = int(self._step_ws[(nbytes - 256) // 4].item())
         assert status == 0, f"decode step left work undone (status {status})"
-        assert int(self._step_ws[:16].abs().max().item()) == 0   # counters re-armed
+        assert int(self._step_ws[:64 * self.B * self.H].abs().max().item()) == 0   # counters re-armed
         return (self.scores.cpu().numpy(), idx.cpu().numpy(), keff.cpu().numpy(),
                 out.cpu().numpy(), lse.cpu().numpy())
 
