@@ -150,21 +150,18 @@ __global__ __launch_bounds__(kStepThreads, 4) void step_kernel(const StepArgs a)
     __syncthreads();
   }
   STEP_TRACE(2);
-#ifdef QUEST_STEP_TRACE
-  if (tid == 0 && a.trace) {
-    a.trace[(size_t)blockIdx.x * 16 + 8] = fenced ? 1 : 2;
-    a.trace[(size_t)blockIdx.x * 16 + 9] = die + 100;
-    a.trace[(size_t)blockIdx.x * 16 + 10] = ((uint64_t)sm.u[1] << 32) | sm.u[0];
-    a.trace[(size_t)blockIdx.x * 16 + 11] = seen;
-  }
-#endif
 
   // ---- 2. the member that finished the head's estimate selects its pages
   if (last_est) {
     if (fenced) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     topk_block<kStepThreads, kItems, true>(
         sm.topk, a.est.scores + (size_t)item * max_pages, a.est.seq_lens + b, max_pages, a.k_pages,
-        a.topk_idx + (size_t)item * a.k_pages, (h == 0 && a.k_eff != nullptr) ? a.k_eff + b : nullptr);
+        a.topk_idx + (size_t)item * a.k_pages, (h == 0 && a.k_eff != nullptr) ? a.k_eff + b : nullptr
+#ifdef QUEST_STEP_TRACE
+        ,
+        a.trace ? a.trace + (size_t)blockIdx.x * 16 + 8 : nullptr
+#endif
+    );
     wait_stores();
     __syncthreads();
     if (M > 1 && tid == 0) {
