@@ -66,9 +66,11 @@ typedef enum quest_status {
 
 /* quest_cache.flags.  Neither flag changes any result.
  *  QUEST_FLAG_PERSISTENT_STEP: quest_decode_step runs the whole step as one
- *    persistent launch (per-die task queues) instead of three launches; it is
- *    slower than the three launches at the sizes measured so far and is kept
- *    selectable for tuning.
+ *    launch instead of three whenever the shape allows it (see there).  Its
+ *    work-groups wait for each other inside the launch, so it wants the GPU to
+ *    itself for those microseconds: if other work keeps part of the grid from
+ *    becoming resident, a bounded wait expires and the call reports it through
+ *    the status word (never a hang).
  *  QUEST_FLAG_DEVICE_FENCES: work-groups that exchange partial results inside a
  *    launch always use device-scope release/acquire fences, as they do on their
  *    own when they find themselves on different dies (for testing that path). */
@@ -174,8 +176,8 @@ int quest_sparse_decode(const quest_cache* cache, const void* q, const int32_t* 
  * one buffer of max(both sizes) may serve both calls); calls sharing a
  * workspace must not overlap in time.  The 32-bit word at byte offset n - 256
  * is a sticky status: 0 = every launch so far completed all its work; non-zero
- * = an internal bounded wait of the persistent launch expired and the outputs
- * of that launch must not be used.
+ * = an internal bounded wait of the single launch expired; the outputs of that
+ * launch must not be used and the workspace must be zero-filled again.
  * By default the call enqueues the three launches named above (one host call
  * instead of three); with QUEST_FLAG_PERSISTENT_STEP, when every (sequence,
  * head) can have its team of work-groups resident at once and

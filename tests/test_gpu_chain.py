@@ -137,7 +137,7 @@ def run_single_launch_steps(w, steps, permute, flags):
     assert np.array_equal(one.np16(one.v_pool).view(np.uint16), ref.np16(ref.v_pool).view(np.uint16))
 
 
-STEP_FLAGS = [0, 1, 2]      # three launches / persistent launch / three launches with device fences
+STEP_FLAGS = [0, 1, 2, 3]   # three launches / single launch / the same two with device fences forced
 
 
 @pytest.mark.parametrize("flags", STEP_FLAGS)
