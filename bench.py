@@ -41,6 +41,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--layers", type=int, default=16, help="distinct layer buffers to rotate over")
     ap.add_argument("--config", type=int, default=1, help="workload id (1 = headline)")
+    ap.add_argument("--page-size", type=int, default=0,
+                    help="tokens per page (8, 16, 32, 64) instead of the workload's own; same "
+                         "context and token budget (the page-size sweep of the paper's Figure 8)")
     ap.add_argument("--repeats", type=int, default=5, help="graph replays; the median is reported")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="also time eager (per-call) launches")
@@ -62,7 +65,8 @@ def main():
     n_total = args.warmup + args.steps
     n_layers = args.layers
     visits = -(-n_total // n_layers)                      # appends per layer buffer
-    w = synth.workload(args.config, decode_steps=visits + 1)
+    over = {"page_size": args.page_size} if args.page_size else {}
+    w = synth.workload(args.config, decode_steps=visits + 1, **over)
     B, H, S, D, K = w.batch, w.num_heads, w.page_size, w.head_dim, w.k_pages
     scale = 1.0 / math.sqrt(D)
 
@@ -206,8 +210,9 @@ def main():
     pages_steps = [int(sum(-(-int(x) // S) for x in lens_steps[i])) for i in timed]
     meta_bytes = float(np.mean([H * p * 512 for p in pages_steps]))
     ksel = [sum(min(K, -(-int(x) // S)) for x in lens_steps[i]) for i in timed]
-    kv_bytes = float(np.mean([H * k * 8192 for k in ksel]))
-    dense_bytes = float(np.mean([H * p * 8192 for p in pages_steps]))
+    page_bytes = 2 * S * D * 2                            # keys + values of one (page, head)
+    kv_bytes = float(np.mean([H * k * page_bytes for k in ksel]))
+    dense_bytes = float(np.mean([H * p * page_bytes for p in pages_steps]))
     step_bytes = meta_bytes + kv_bytes
     gbps = step_bytes / (us_step * 1e-6) / 1e9
 

@@ -28,8 +28,9 @@
  *   - fp16 means IEEE binary16.  Keys, values and queries must be finite
  *     (NaN/Inf in a *valid* slot is undefined behaviour; stale slots beyond
  *     seq_lens are never used, whatever they contain).
- *   - Supported shapes: head_dim == 128, page_size == 16, multi-head attention
- *     (one KV head per query head).
+ *   - Supported shapes: head_dim == 128; page_size 8, 16, 32 or 64 tokens (the
+ *     paper's default is 16; Figure 8 sweeps the page size); multi-head
+ *     attention (one KV head per query head).
  *
  * Layouts (row-major, innermost last)
  *   k_pool, v_pool : fp16  [num_phys_pages][num_heads][page_size][head_dim]
@@ -59,7 +60,7 @@ typedef enum quest_status {
   QUEST_OK = 0,
   QUEST_ERR_NULL = -1,        /* a required pointer is NULL                  */
   QUEST_ERR_SHAPE = -2,       /* a size is < 1 or exceeds a launch limit     */
-  QUEST_ERR_UNSUPPORTED = -3, /* head_dim != 128 or page_size != 16          */
+  QUEST_ERR_UNSUPPORTED = -3, /* head_dim != 128, page_size not 8/16/32/64    */
   QUEST_ERR_WORKSPACE = -4,   /* workspace NULL or smaller than required     */
   QUEST_ERR_HIP = -5          /* the HIP runtime refused the launch          */
 } quest_status;
@@ -82,7 +83,7 @@ typedef struct quest_cache {
   int32_t batch;              /* B >= 1                                      */
   int32_t num_heads;          /* H >= 1                                      */
   int32_t head_dim;           /* D, must be 128                              */
-  int32_t page_size;          /* S, must be 16                               */
+  int32_t page_size;          /* S: 8, 16, 32 or 64                          */
   int32_t max_pages_per_seq;  /* row stride of page_table and of scores      */
   int32_t flags;              /* QUEST_FLAG_* bits, normally 0               */
   int64_t num_phys_pages;     /* capacity of the pools, in pages             */
@@ -179,9 +180,9 @@ int quest_sparse_decode(const quest_cache* cache, const void* q, const int32_t* 
  * = an internal bounded wait of the single launch expired; the outputs of that
  * launch must not be used and the workspace must be zero-filled again.
  * By default the call enqueues the three launches named above (one host call
- * instead of three); with QUEST_FLAG_PERSISTENT_STEP, when every (sequence,
- * head) can have its team of work-groups resident at once and
- * max_pages_per_seq <= 8192, it is a single launch. */
+ * instead of three); with QUEST_FLAG_PERSISTENT_STEP, when page_size == 16,
+ * every (sequence, head) can have its team of work-groups resident at once
+ * and max_pages_per_seq <= 8192, it is a single launch. */
 int quest_step_workspace_bytes(const quest_cache* cache, int32_t k_pages, size_t* out_bytes);
 int quest_decode_step(const quest_cache* cache, const void* k_new, const void* v_new,
                       int32_t k_pool_write, const void* q, int32_t k_pages, float sm_scale,

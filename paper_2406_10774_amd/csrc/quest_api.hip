@@ -32,9 +32,9 @@ int check_cache(const quest_cache* c, const char* who) {
     set_error("%s: cache is NULL", who);
     return QUEST_ERR_NULL;
   }
-  if (c->head_dim != kHeadDim || c->page_size != kPageSize) {
-    set_error("%s: only head_dim == 128 and page_size == 16 are supported (got %d, %d)", who,
-              c->head_dim, c->page_size);
+  if (c->head_dim != kHeadDim || page_shift_of(c->page_size) < 0) {
+    set_error("%s: only head_dim == 128 and page_size 8, 16, 32 or 64 are supported (got %d, %d)",
+              who, c->head_dim, c->page_size);
     return QUEST_ERR_UNSUPPORTED;
   }
   if (c->batch < 1 || c->num_heads < 1 || c->max_pages_per_seq < 1 || c->num_phys_pages < 1) {
@@ -45,7 +45,7 @@ int check_cache(const quest_cache* c, const char* who) {
     set_error("%s: batch and num_heads are limited to 65535 (grid dimensions)", who);
     return QUEST_ERR_SHAPE;
   }
-  if ((int64_t)c->max_pages_per_seq * kPageSize > INT32_MAX) {
+  if ((int64_t)c->max_pages_per_seq * c->page_size > INT32_MAX) {
     set_error("%s: max_pages_per_seq * page_size exceeds the int32 range of seq_lens", who);
     return QUEST_ERR_SHAPE;
   }

@@ -11,10 +11,17 @@
 namespace quest {
 
 constexpr int kHeadDim = 128;   // D: channels per head
-constexpr int kPageSize = 16;   // S: tokens per page
+constexpr int kPageSize = 16;   // S: tokens per page the single-launch step is built for
 constexpr int kWave = 64;
-// One (page, head) block of keys (or of values) is S*D fp16 = 4 KiB = 4 wave-wide
-// 16-byte loads; one metadata entry (min row + max row) is 512 B.  The metadata
+constexpr int kRowBytes = kHeadDim * 2;  // one token's key (or value) of one head
+
+// Supported page sizes: 8, 16, 32, 64 tokens (the sweep of Figure 8 of arXiv
+// 2406.10774 covers these); kernels take log2(S).  Returns -1 for others.
+inline int page_shift_of(int page_size) {
+  return page_size == 8 ? 3 : page_size == 16 ? 4 : page_size == 32 ? 5 : page_size == 64 ? 6 : -1;
+}
+// One (page, head) block of keys (or of values) is S*D fp16 (4 KiB at S = 16 = 4
+// wave-wide 16-byte loads); one metadata entry (min row + max row) is 512 B.  The metadata
 // table is head-major, [H][num_phys_pages]: the estimate scans every page of a
 // head, and consecutive physical pages of one head are then contiguous (with
 // page-major entries the same scan touches 512 B every 16 KiB, measured 25 %

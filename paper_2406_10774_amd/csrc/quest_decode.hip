@@ -60,6 +60,8 @@ struct DecodeArgs {
   int list_len;             // entries of the page list the splits divide: k_pages, or max_pages
   int per_split;            // ceil(list_len / splits)
   int force_device_fences;  // debug: take the cross-die exchange path
+  int page_shift;           // log2(tokens per page)
+  int unit_shift;           // log2(streaming units per page): 0 up to 16 tokens, 1 for 32, 2 for 64
   float scale_log2;         // sm_scale * log2(e)
 #ifdef QUEST_STEP_TRACE
   unsigned long long* trace;
@@ -74,6 +76,7 @@ struct DecodeArgs {
 // The placement is verified at run time (see quest_team.h): if the splits of a
 // head do not all run on one die, the exchange falls back to device-scope
 // release/acquire fences: slow, still correct.
+template <int kLoads>  // wave-wide 16-byte loads per unit of keys (and of values): 4, or 2 for 8-token pages
 __global__ __launch_bounds__(kDecThreads) void decode_split_kernel(const DecodeArgs a) {
   __shared__ float sm_acc[kDecWaves][kHeadDim];
   __shared__ float sm_m[kDecWaves], sm_l[kDecWaves];
@@ -115,34 +118,44 @@ __global__ __launch_bounds__(kDecThreads) void decode_split_kernel(const DecodeA
 #pragma unroll
   for (int j = 0; j < 8; ++j) st.acc[j] = 0.f;
 
-  for (int chunk = 0; chunk < iters; chunk += kWave) {
-    // lane i holds list entry chunk + i of this wave: logical page and physical page
-    const int pos = begin + wave + kDecWaves * (chunk + lane);
+  // A page is streamed as 1 << unit_shift units of up to 16 tokens; lane i of a
+  // round holds unit i of this wave: list entry i >> unit_shift, unit i & mask.
+  const int units = iters << a.unit_shift;
+  const int num_pages = (seq_len + (1 << a.page_shift) - 1) >> a.page_shift;
+  for (int chunk = 0; chunk < units; chunk += kWave) {
+    const int u = chunk + lane;
+    const int e = u >> a.unit_shift;
+    const int un_v = u & ((1 << a.unit_shift) - 1);
+    const int pos = begin + wave + kDecWaves * e;
     int lp_v = -1;
-    if (chunk + lane < iters && pos < end) lp_v = idx_row ? idx_row[pos] : pos;
+    if (e < iters && pos < end) lp_v = idx_row ? idx_row[pos] : pos;
     int ph_v = 0;
     if (lp_v >= 0 && lp_v < a.max_pages) ph_v = pt[lp_v];
-    const int num_pages = (seq_len + kPageSize - 1) / kPageSize;
     if (lp_v >= num_pages) lp_v = -1;
-    const int n_here = min(kWave, iters - chunk);
+    const int n_here = min(kWave, units - chunk);
     if (__builtin_amdgcn_readlane(ph_v, 0) >= 0) DEC_TRACE(1);
 
-    PageRegs ra, rb;
+#define QUEST_LOAD_UNIT(regs, i)                                                               \
+  load_unit<kLoads>(regs, a.k_pool, a.v_pool, a.num_heads, h, seq_len, __builtin_amdgcn_readlane(lp_v, i), \
+                    __builtin_amdgcn_readlane(ph_v, i), __builtin_amdgcn_readlane(un_v, i),    \
+                    a.page_shift, lane)
+    PageRegsT<kLoads> ra, rb;
     int j = 0;
     int lp = __builtin_amdgcn_readlane(lp_v, 0);
-    if (lp >= 0) load_page(ra, a.k_pool, a.v_pool, a.num_heads, h, seq_len, lp, __builtin_amdgcn_readlane(ph_v, 0), lane);
+    if (lp >= 0) QUEST_LOAD_UNIT(ra, 0);
     while (lp >= 0) {
       int lp_b = -1;
       if (j + 1 < n_here) lp_b = __builtin_amdgcn_readlane(lp_v, j + 1);
-      if (lp_b >= 0) load_page(rb, a.k_pool, a.v_pool, a.num_heads, h, seq_len, lp_b, __builtin_amdgcn_readlane(ph_v, j + 1), lane);
+      if (lp_b >= 0) QUEST_LOAD_UNIT(rb, j + 1);
       fold_page(st, ra, qv, a.scale_log2, grp);
       if (lp_b < 0) break;
       j += 2;
       lp = -1;
       if (j < n_here) lp = __builtin_amdgcn_readlane(lp_v, j);
-      if (lp >= 0) load_page(ra, a.k_pool, a.v_pool, a.num_heads, h, seq_len, lp, __builtin_amdgcn_readlane(ph_v, j), lane);
+      if (lp >= 0) QUEST_LOAD_UNIT(ra, j);
       fold_page(st, rb, qv, a.scale_log2, grp);
     }
+#undef QUEST_LOAD_UNIT
   }
 
   // the four DPP rows of the wave, then the four waves of the group
@@ -244,8 +257,8 @@ int env_int(const char* name, int fallback) {
 
 }  // namespace
 
-// Number of splits of a head's page list.  A split holds at least sixteen pages
-// (four per wave, two in flight at a time), and the whole launch stays within
+// Number of splits of a head's page list.  A split holds at least 256 tokens (sixteen
+// pages of 16: four per wave, two in flight at a time), and the whole launch stays within
 // the ~1000 work-groups that are resident at once, so that all splits of a head
 // start together (the condition for the cheap same-die exchange) and the
 // merge reads few partial results.  Both knobs can be overridden through the
@@ -261,7 +274,12 @@ SplitPlan plan_splits(const quest_cache& c, int k_pages) {
   p.list_len = k_pages > 0 ? (k_pages < c.max_pages_per_seq ? k_pages : c.max_pages_per_seq)
                            : c.max_pages_per_seq;
   const long bh = (long)c.batch * c.num_heads;
-  long splits = (p.list_len + pages_per_split - 1) / pages_per_split;
+  // the knob is in pages of 16 tokens: the same bytes per split for every page size
+  const int shift = page_shift_of(c.page_size);
+  const long pps = shift >= 0 && ((long)pages_per_split << 4 >> shift) > 0
+                       ? ((long)pages_per_split << 4 >> shift)
+                       : 1;
+  long splits = (p.list_len + pps - 1) / pps;
   const long cap = max_groups / bh > 0 ? max_groups / bh : 1;
   if (splits > cap) splits = cap;
   if (splits < 1) splits = 1;
@@ -308,6 +326,8 @@ int launch_sparse_decode(const quest_cache& c, const void* q, const int32_t* top
   a.out_is_fp16 = out_is_fp16;
   a.lse = lse;
   a.scale_log2 = sm_scale * kLog2e;
+  a.page_shift = page_shift_of(c.page_size);
+  a.unit_shift = a.page_shift > 4 ? a.page_shift - 4 : 0;
 #ifdef QUEST_STEP_TRACE
   a.trace = std::getenv("QUEST_STEP_TRACE_PTR")
                 ? (unsigned long long*)std::strtoull(std::getenv("QUEST_STEP_TRACE_PTR"), nullptr, 16)
@@ -318,8 +338,11 @@ int launch_sparse_decode(const quest_cache& c, const void* q, const int32_t* top
   a.part_acc = workspace ? (float*)((char*)workspace + counter_bytes(c)) : nullptr;
   a.part_ml = a.part_acc ? a.part_acc + n_part * kHeadDim : nullptr;
   const long bh8 = ((long)c.batch * c.num_heads + 7) / 8;
-  hipLaunchKernelGGL(decode_split_kernel, dim3((unsigned)(bh8 * 8 * a.splits)), dim3(kDecThreads), 0, s,
-                     a);
+  const dim3 grid((unsigned)(bh8 * 8 * a.splits));
+  if (c.page_size == 8)
+    hipLaunchKernelGGL(decode_split_kernel<2>, grid, dim3(kDecThreads), 0, s, a);
+  else
+    hipLaunchKernelGGL(decode_split_kernel<4>, grid, dim3(kDecThreads), 0, s, a);
   return check_launch("quest_sparse_decode");
 }
 

@@ -14,10 +14,15 @@ constexpr float kNegBig = -1.0e30f;  // "no token yet": finite, so exp2(m - m) n
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
-struct PageRegs {
-  uint4 k[4], v[4];
+// Registers of one unit of streaming: up to 16 consecutive tokens of one (page,
+// head): kLoads = 4 wave-wide 16-byte loads of keys and 4 of values (2 and 2 for
+// pages of 8 tokens).  Pages of 32 or 64 tokens are walked as 2 or 4 such units.
+template <int kLoads>  // 2 or 4
+struct PageRegsT {
+  uint4 k[kLoads], v[kLoads];
   int n_valid;
 };
+typedef PageRegsT<4> PageRegs;
 
 __device__ __forceinline__ float lo(uint32_t h2) {
   return (float)__builtin_bit_cast(half2_t, h2)[0];
@@ -30,41 +35,60 @@ struct Softmax {
   float m, l, acc[8];
 };
 
+// Unit `unit` (tokens [unit * 4 kLoads, (unit + 1) * 4 kLoads)) of logical page
+// `logical_page`, stored in physical page `phys`; pages hold 1 << page_shift tokens.
+template <int kLoads>
+__device__ __forceinline__ void load_unit(PageRegsT<kLoads>& r, const char* __restrict__ k_pool,
+                                          const char* __restrict__ v_pool, int num_heads, int h,
+                                          int seq_len, int logical_page, int phys, int unit,
+                                          int page_shift, int lane) {
+  const size_t row = (((size_t)phys * num_heads + h) << page_shift) + (size_t)unit * (4 * kLoads);
+  const size_t off = row * kRowBytes + lane * 16;
+#pragma unroll
+  for (int i = 0; i < kLoads; ++i) r.k[i] = ld16(k_pool + off + i * 1024);
+#pragma unroll
+  for (int i = 0; i < kLoads; ++i) r.v[i] = ld16(v_pool + off + i * 1024);
+  r.n_valid = min(4 * kLoads, seq_len - (logical_page << page_shift) - unit * (4 * kLoads));
+}
+
+// A whole page of 16 tokens.
 __device__ __forceinline__ void load_page(PageRegs& r, const char* __restrict__ k_pool,
                                           const char* __restrict__ v_pool, int num_heads, int h,
                                           int seq_len, int logical_page, int phys, int lane) {
-  const size_t off = ((size_t)phys * num_heads + h) * kBlockBytes + lane * 16;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) r.k[i] = ld16(k_pool + off + i * 1024);
-#pragma unroll
-  for (int i = 0; i < 4; ++i) r.v[i] = ld16(v_pool + off + i * 1024);
-  r.n_valid = min(kPageSize, seq_len - logical_page * kPageSize);
+  load_unit<4>(r, k_pool, v_pool, num_heads, h, seq_len, logical_page, phys, 0, 4, lane);
 }
 
-__device__ __forceinline__ void fold_page(Softmax& st, PageRegs& r, const uint4 qv, float scale_log2,
-                                          int grp) {
-  float z[4];
+// n_valid may be anything up to 4 kLoads, also <= 0 (a unit past the end of a
+// partial page): such tokens contribute nothing.
+template <int kLoads>
+__device__ __forceinline__ void fold_page(Softmax& st, PageRegsT<kLoads>& r, const uint4 qv,
+                                          float scale_log2, int grp) {
+  float z[kLoads];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) z[i] = row16_sum(dot8(qv, r.k[i], 0.f)) * scale_log2;
-  if (r.n_valid < kPageSize) {  // partial last page: stale slots contribute nothing
+  for (int i = 0; i < kLoads; ++i) z[i] = row16_sum(dot8(qv, r.k[i], 0.f)) * scale_log2;
+  if (r.n_valid < 4 * kLoads) {  // partial last page: stale slots contribute nothing
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < kLoads; ++i) {
       if (grp + 4 * i >= r.n_valid) {
         z[i] = -INFINITY;
         r.v[i] = make_uint4(0, 0, 0, 0);
       }
     }
   }
-  const float m_new = fmaxf(fmaxf(st.m, fmaxf(z[0], z[1])), fmaxf(z[2], z[3]));
-  const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
-  float p[4];
+  float m_new = st.m;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) p[i] = __builtin_amdgcn_exp2f(z[i] - m_new);
-  st.l = st.l * alpha + ((p[0] + p[1]) + (p[2] + p[3]));
+  for (int i = 0; i < kLoads; ++i) m_new = fmaxf(m_new, z[i]);
+  const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
+  float p[kLoads];
+#pragma unroll
+  for (int i = 0; i < kLoads; ++i) p[i] = __builtin_amdgcn_exp2f(z[i] - m_new);
+  float p_sum = p[0] + p[1];
+  if (kLoads == 4) p_sum += p[kLoads - 2] + p[kLoads - 1];
+  st.l = st.l * alpha + p_sum;
 #pragma unroll
   for (int j = 0; j < 8; ++j) st.acc[j] *= alpha;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < kLoads; ++i) {
     st.acc[0] += p[i] * lo(r.v[i].x);
     st.acc[1] += p[i] * hi(r.v[i].x);
     st.acc[2] += p[i] * lo(r.v[i].y);

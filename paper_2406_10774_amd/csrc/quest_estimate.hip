@@ -40,6 +40,7 @@ EstimateArgs make_args(const quest_cache& c, const void* q, float* scores) {
   a.num_heads = c.num_heads;
   a.max_pages = c.max_pages_per_seq;
   a.num_phys_pages = c.num_phys_pages;
+  a.page_shift = page_shift_of(c.page_size);
   a.k_new = a.v_new = nullptr;
   a.k_pool = a.v_pool = nullptr;
   a.k_pool_write = 0;

@@ -28,6 +28,7 @@ struct EstimateArgs {
   char* k_pool;
   char* v_pool;
   int k_pool_write;
+  int page_shift;  // log2(tokens per page)
 };
 
 // One wave scores the 4 * kIters logical pages starting at `base` of (sequence b,
@@ -62,7 +63,8 @@ __device__ __forceinline__ void estimate_wave(const EstimateArgs& a, int b, int 
     phys[it] = p < max_pages ? pt[p] : 0;
   }
   const uint4 qv = ld16(q + bh * (kHeadDim * 2) + c * 16);
-  const int num_pages = (seq_len + kPageSize - 1) / kPageSize;
+  const int page_shift = a.page_shift;
+  const int num_pages = (seq_len + (1 << page_shift) - 1) >> page_shift;
   if (base >= num_pages) return;
 
   uint4 mn[kIters], mx[kIters];
@@ -80,9 +82,9 @@ __device__ __forceinline__ void estimate_wave(const EstimateArgs& a, int b, int 
 
   if (kAppend) {
     const int pos = seq_len - 1;
-    const int last = pos / kPageSize;
+    const int last = pos >> page_shift;
     if (last >= base && last < base + 4 * kIters) {  // wave-uniform
-      const int slot = pos - last * kPageSize;
+      const int slot = pos - (last << page_shift);
       const uint4 kn = ld16(k_new + bh * (kHeadDim * 2) + c * 16);
       const uint4 key = order_key8(kn);
 #pragma unroll
@@ -90,7 +92,7 @@ __device__ __forceinline__ void estimate_wave(const EstimateArgs& a, int b, int 
         if (base + kIters * grp + it == last) {
           const size_t ph = (size_t)phys[it] * num_heads + h;
           if (k_pool_write) {
-            const size_t off = ph * kBlockBytes + (size_t)slot * (kHeadDim * 2) + c * 16;
+            const size_t off = ((ph << page_shift) + slot) * kRowBytes + c * 16;
             st16(k_pool + off, kn);
             st16(v_pool + off, ld16(v_new + bh * (kHeadDim * 2) + c * 16));
           }

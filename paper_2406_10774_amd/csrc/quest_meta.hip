@@ -13,49 +13,52 @@ namespace quest {
 namespace {
 
 constexpr int kBuildWaves = 4;          // waves per work-group
-constexpr int kBuildPagesPerWave = 4;   // (page, head) key blocks per wave, all loads issued up front
-constexpr int kBuildPagesPerGroup = kBuildWaves * kBuildPagesPerWave;
+constexpr int kBuildLoads = 16;         // wave-wide 16-byte loads a wave issues up front (16 KiB)
 
 constexpr uint32_t kKeyMax2 = 0x7fff7fffu;  // identity of min
 constexpr uint32_t kKeyMin2 = 0x80008000u;  // identity of max
 
-// One wave reduces one 4 KiB key block.  Lane l holds channels 8*(l%16)..+7 of
-// tokens l/16 + 4r (r = 0..3): load r of the wave is the contiguous 1 KiB
-// [r*1024, r*1024+1024) of the block, 16 bytes per lane.
+// One wave reduces kBuildLoads / (kS / 4) key blocks of kS tokens each (4 blocks of
+// 4 KiB at the paper's page size of 16).  Lane l holds channels 8*(l%16)..+7 of
+// tokens l/16 + 4r (r = 0..kS/4-1): load r of a block is its contiguous 1 KiB
+// [r*1024, r*1024+1024), 16 bytes per lane.
+template <int kS>
 __global__ __launch_bounds__(kBuildWaves* kWave) void build_meta_kernel(
     const char* __restrict__ k_pool, char* __restrict__ meta, const int32_t* __restrict__ page_table,
     const int32_t* __restrict__ seq_lens, int num_heads, int max_pages, int64_t num_phys_pages) {
+  constexpr int kLoads = kS / 4;                        // per block
+  constexpr int kPagesPerWave = kBuildLoads / kLoads;   // 8, 4, 2, 1
   const int b = blockIdx.z;
   const int h = blockIdx.y;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = lane_id();
   const int grp = lane >> 4;
   const int seq_len = seq_lens[b];
-  const int num_pages = (seq_len + kPageSize - 1) / kPageSize;
-  const int page0 = (blockIdx.x * kBuildWaves + wave) * kBuildPagesPerWave;
+  const int num_pages = (seq_len + kS - 1) / kS;
+  const int page0 = (blockIdx.x * kBuildWaves + wave) * kPagesPerWave;
   if (page0 >= num_pages) return;
 
-  uint4 buf[kBuildPagesPerWave][4];
-  int phys[kBuildPagesPerWave];
+  uint4 buf[kPagesPerWave][kLoads];
+  int phys[kPagesPerWave];
 #pragma unroll
-  for (int u = 0; u < kBuildPagesPerWave; ++u) {
+  for (int u = 0; u < kPagesPerWave; ++u) {
     const int p = page0 + u;
     if (p < num_pages) {
       phys[u] = page_table[(size_t)b * max_pages + p];
-      const char* blk = k_pool + ((size_t)phys[u] * num_heads + h) * kBlockBytes;
+      const char* blk = k_pool + ((size_t)phys[u] * num_heads + h) * (kS * kRowBytes);
 #pragma unroll
-      for (int r = 0; r < 4; ++r) buf[u][r] = ld16(blk + r * 1024 + lane * 16);
+      for (int r = 0; r < kLoads; ++r) buf[u][r] = ld16(blk + r * 1024 + lane * 16);
     }
   }
 #pragma unroll
-  for (int u = 0; u < kBuildPagesPerWave; ++u) {
+  for (int u = 0; u < kPagesPerWave; ++u) {
     const int p = page0 + u;
     if (p >= num_pages) break;
-    const int n_valid = min(kPageSize, seq_len - p * kPageSize);
+    const int n_valid = min(kS, seq_len - p * kS);
     uint4 mn = make_uint4(kKeyMax2, kKeyMax2, kKeyMax2, kKeyMax2);
     uint4 mx = make_uint4(kKeyMin2, kKeyMin2, kKeyMin2, kKeyMin2);
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
+    for (int r = 0; r < kLoads; ++r) {
       if (grp + 4 * r < n_valid) {  // stale slots of a partial page never take part
         const uint4 key = order_key8(buf[u][r]);
         mn = key_min8(mn, key);
@@ -78,7 +81,7 @@ __global__ __launch_bounds__(256) void append_meta_kernel(
     char* __restrict__ k_pool, char* __restrict__ v_pool, char* __restrict__ meta,
     const int32_t* __restrict__ page_table, const int32_t* __restrict__ seq_lens,
     const char* __restrict__ k_new, const char* __restrict__ v_new, int batch, int num_heads,
-    int max_pages, int k_pool_write, int64_t num_phys_pages) {
+    int max_pages, int k_pool_write, int64_t num_phys_pages, int page_shift) {
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
   const int bh = t >> 4;
   const int c = t & 15;
@@ -86,14 +89,14 @@ __global__ __launch_bounds__(256) void append_meta_kernel(
   const int b = bh / num_heads;
   const int h = bh - b * num_heads;
   const int pos = seq_lens[b] - 1;
-  const int page = pos / kPageSize;
-  const int slot = pos - page * kPageSize;
+  const int page = pos >> page_shift;
+  const int slot = pos - (page << page_shift);
   const int phys = page_table[(size_t)b * max_pages + page];
   const size_t ph = (size_t)phys * num_heads + h;
 
   const uint4 k = ld16(k_new + (size_t)bh * (kHeadDim * 2) + c * 16);
   if (k_pool_write) {
-    const size_t off = ph * kBlockBytes + (size_t)slot * (kHeadDim * 2) + c * 16;
+    const size_t off = ((ph << page_shift) + slot) * kRowBytes + c * 16;
     st16(k_pool + off, k);
     st16(v_pool + off, ld16(v_new + (size_t)bh * (kHeadDim * 2) + c * 16));
   }
@@ -112,13 +115,23 @@ __global__ __launch_bounds__(256) void append_meta_kernel(
 
 }  // namespace
 
-int launch_build_meta(const quest_cache& c, hipStream_t s) {
-  dim3 grid((c.max_pages_per_seq + kBuildPagesPerGroup - 1) / kBuildPagesPerGroup, c.num_heads,
-            c.batch);
-  hipLaunchKernelGGL(build_meta_kernel, grid, dim3(kBuildWaves * kWave), 0, s,
+template <int kS>
+int launch_build_meta_for(const quest_cache& c, hipStream_t s) {
+  constexpr int kPagesPerGroup = kBuildWaves * (kBuildLoads / (kS / 4));
+  dim3 grid((c.max_pages_per_seq + kPagesPerGroup - 1) / kPagesPerGroup, c.num_heads, c.batch);
+  hipLaunchKernelGGL(build_meta_kernel<kS>, grid, dim3(kBuildWaves * kWave), 0, s,
                      (const char*)c.k_pool, (char*)c.meta, c.page_table, c.seq_lens, c.num_heads,
                      c.max_pages_per_seq, c.num_phys_pages);
   return check_launch("quest_build_meta");
+}
+
+int launch_build_meta(const quest_cache& c, hipStream_t s) {
+  switch (c.page_size) {
+    case 8: return launch_build_meta_for<8>(c, s);
+    case 32: return launch_build_meta_for<32>(c, s);
+    case 64: return launch_build_meta_for<64>(c, s);
+    default: return launch_build_meta_for<16>(c, s);
+  }
 }
 
 int launch_append_meta(const quest_cache& c, const void* k_new, const void* v_new, int k_pool_write,
@@ -127,7 +140,8 @@ int launch_append_meta(const quest_cache& c, const void* k_new, const void* v_ne
   hipLaunchKernelGGL(append_meta_kernel, dim3((threads + 255) / 256), dim3(256), 0, s,
                      (char*)c.k_pool, (char*)c.v_pool, (char*)c.meta, c.page_table, c.seq_lens,
                      (const char*)k_new, (const char*)v_new, c.batch, c.num_heads,
-                     c.max_pages_per_seq, k_pool_write, c.num_phys_pages);
+                     c.max_pages_per_seq, k_pool_write, c.num_phys_pages,
+                     page_shift_of(c.page_size));
   return check_launch("quest_append_meta");
 }
 

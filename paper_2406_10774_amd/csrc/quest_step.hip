@@ -156,7 +156,8 @@ __global__ __launch_bounds__(kStepThreads, 4) void step_kernel(const StepArgs a)
     if (fenced) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     topk_block<kStepThreads, kItems, true>(
         sm.topk, a.est.scores + (size_t)item * max_pages, a.est.seq_lens + b, max_pages, a.k_pages,
-        a.topk_idx + (size_t)item * a.k_pages, (h == 0 && a.k_eff != nullptr) ? a.k_eff + b : nullptr
+        a.topk_idx + (size_t)item * a.k_pages, (h == 0 && a.k_eff != nullptr) ? a.k_eff + b : nullptr,
+        a.est.page_shift
 #ifdef QUEST_STEP_TRACE
         ,
         a.trace ? a.trace + (size_t)blockIdx.x * 16 + 8 : nullptr
@@ -355,9 +356,9 @@ StepPlan plan_step(const quest_cache& c, int k_pages) {
   StepPlan p = {};
   const long items = (long)c.batch * c.num_heads;
   const int cap = resident_capacity();
-  // opt-in, rows within the in-register selection, every team resident at once
-  p.fused = (c.flags & QUEST_FLAG_PERSISTENT_STEP) && cap > 0 && items <= cap &&
-            c.max_pages_per_seq <= kStepThreads * 16;
+  // opt-in, 16-token pages, rows within the in-register selection, every team resident at once
+  p.fused = (c.flags & QUEST_FLAG_PERSISTENT_STEP) && c.page_size == kPageSize && cap > 0 &&
+            items <= cap && c.max_pages_per_seq <= kStepThreads * 16;
   if (!p.fused) return p;
   const int mp = c.max_pages_per_seq;
   static const int force_iters = env_int("QUEST_STEP_EST_ITERS", 0);
@@ -450,6 +451,7 @@ int launch_decode_step(const quest_cache& c, const void* k_new, const void* v_ne
   a.est.num_heads = c.num_heads;
   a.est.max_pages = c.max_pages_per_seq;
   a.est.num_phys_pages = c.num_phys_pages;
+  a.est.page_shift = page_shift_of(c.page_size);
   a.est.k_new = (const char*)k_new;
   a.est.v_new = (const char*)v_new;
   a.est.k_pool = (char*)c.k_pool;

@@ -29,14 +29,14 @@ template <int kThreads, int kItems>
 __global__ __launch_bounds__(kThreads) void topk_kernel(
     const float* __restrict__ scores, const int32_t* __restrict__ seq_lens,
     int32_t* __restrict__ topk_idx, int32_t* __restrict__ k_eff, int num_heads, int max_pages,
-    int k_pages) {
+    int k_pages, int page_shift) {
   __shared__ TopkShared<kThreads> sm;
   const int h = blockIdx.x;
   const int b = blockIdx.y;
   const size_t bh = (size_t)b * num_heads + h;
   topk_block<kThreads, kItems, false>(sm, scores + bh * max_pages, seq_lens + b, max_pages, k_pages,
                                       topk_idx + bh * k_pages,
-                                      (h == 0 && k_eff != nullptr) ? k_eff + b : nullptr);
+                                      (h == 0 && k_eff != nullptr) ? k_eff + b : nullptr, page_shift);
 }
 
 // Fallback for rows too long for register-resident keys: keys are re-read from
@@ -45,7 +45,7 @@ constexpr int kBigThreads = 1024;
 __global__ __launch_bounds__(kBigThreads) void topk_big_kernel(
     const float* __restrict__ scores, const int32_t* __restrict__ seq_lens,
     int32_t* __restrict__ topk_idx, int32_t* __restrict__ k_eff, int num_heads, int max_pages,
-    int k_pages) {
+    int k_pages, int page_shift) {
   constexpr int kWaves = kBigThreads / kWave;
   __shared__ uint32_t hist[256];
   __shared__ int wave_gt[kWaves], wave_eq[kWaves];
@@ -54,7 +54,7 @@ __global__ __launch_bounds__(kBigThreads) void topk_big_kernel(
   const int tid = threadIdx.x;
   const int lane = lane_id();
   const int wave = tid >> 6;
-  const int num_pages = (seq_lens[b] + kPageSize - 1) / kPageSize;
+  const int num_pages = (seq_lens[b] + (1 << page_shift) - 1) >> page_shift;
   const int K = min(k_pages, num_pages);
   const float* row = scores + ((size_t)b * num_heads + h) * max_pages;
   int32_t* out = topk_idx + ((size_t)b * num_heads + h) * k_pages;
@@ -121,7 +121,7 @@ int launch_one(const quest_cache& c, const float* scores, int k_pages, int32_t* 
                int32_t* k_eff, hipStream_t s) {
   hipLaunchKernelGGL((topk_kernel<kThreads, kItems>), dim3(c.num_heads, c.batch), dim3(kThreads), 0,
                      s, scores, c.seq_lens, topk_idx, k_eff, c.num_heads, c.max_pages_per_seq,
-                     k_pages);
+                     k_pages, page_shift_of(c.page_size));
   return check_launch("quest_topk");
 }
 
@@ -152,7 +152,8 @@ int launch_topk(const quest_cache& c, const float* scores, int k_pages, int32_t*
   if (mp < 65536) return launch_one<1024, 64>(c, scores, k_pages, topk_idx, k_eff, s);
 #undef QUEST_TOPK_CASE
   hipLaunchKernelGGL(topk_big_kernel, dim3(c.num_heads, c.batch), dim3(kBigThreads), 0, s, scores,
-                     c.seq_lens, topk_idx, k_eff, c.num_heads, c.max_pages_per_seq, k_pages);
+                     c.seq_lens, topk_idx, k_eff, c.num_heads, c.max_pages_per_seq, k_pages,
+                     page_shift_of(c.page_size));
   return check_launch("quest_topk");
 }
 

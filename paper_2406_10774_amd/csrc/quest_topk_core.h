@@ -84,7 +84,7 @@ template <int kThreads, int kItems, bool kL2Loads>
 __device__ __forceinline__ void topk_block(TopkShared<kThreads>& sm, const float* __restrict__ row,
                                            const int32_t* __restrict__ seq_len_ptr, int max_pages,
                                            int k_pages, int32_t* __restrict__ out,
-                                           int32_t* __restrict__ k_eff_slot,
+                                           int32_t* __restrict__ k_eff_slot, int page_shift,
                                            unsigned long long* trace = nullptr) {
   constexpr int kWaves = kThreads / kWave;
   (void)trace;
@@ -113,7 +113,7 @@ __device__ __forceinline__ void topk_block(TopkShared<kThreads>& sm, const float
   if (tid == 0) vote = 0;
   __syncthreads();
 
-  const int num_pages = (seq_len + kPageSize - 1) / kPageSize;
+  const int num_pages = (seq_len + (1 << page_shift) - 1) >> page_shift;
   const int K = min(k_pages, num_pages);
   if (tid == 0 && k_eff_slot != nullptr) *k_eff_slot = K;
   if (K == num_pages) {  // everything is selected: identity list, padded with -1

@@ -48,7 +48,7 @@ def test_workspace_bytes_is_pure_and_consistent():
 
 
 @pytest.mark.parametrize("kw,status", [
-    (dict(head_dim=64), -3), (dict(page_size=32), -3), (dict(batch=0), -2),
+    (dict(head_dim=64), -3), (dict(page_size=24), -3), (dict(page_size=128), -3), (dict(batch=0), -2),
     (dict(num_heads=70000), -2), (dict(page_table=None), -1), (dict(seq_lens=None), -1),
     (dict(max_pages_per_seq=0), -2),
 ])
