@@ -65,7 +65,7 @@ typedef enum quest_status {
   QUEST_ERR_HIP = -5          /* the HIP runtime refused the launch          */
 } quest_status;
 
-/* quest_cache.flags.  Neither flag changes any result.
+/* quest_cache.flags.  The first two change no result.
  *  QUEST_FLAG_PERSISTENT_STEP: quest_decode_step runs the whole step as one
  *    launch instead of three whenever the shape allows it (see there).  Its
  *    work-groups wait for each other inside the launch, so it wants the GPU to
@@ -74,8 +74,20 @@ typedef enum quest_status {
  *    the status word (never a hang).
  *  QUEST_FLAG_DEVICE_FENCES: work-groups that exchange partial results inside a
  *    launch always use device-scope release/acquire fences, as they do on their
- *    own when they find themselves on different dies (for testing that path). */
-enum { QUEST_FLAG_PERSISTENT_STEP = 1, QUEST_FLAG_DEVICE_FENCES = 2 };
+ *    own when they find themselves on different dies (for testing that path).
+ *  QUEST_FLAG_KEEP_FIRST_PAGE, QUEST_FLAG_KEEP_NEWEST_PAGE: selection policy of
+ *    quest_topk and quest_decode_step.  The paper selects purely by score
+ *    (Section 3.4) and that is the default; with these flags logical page 0
+ *    (the first tokens of the sequence) and / or the page that holds the newest
+ *    token are in the list whatever their score: they rank above every score
+ *    and among themselves by page index, so they take the first places of the K
+ *    and the remaining places are filled by score. */
+enum {
+  QUEST_FLAG_PERSISTENT_STEP = 1,
+  QUEST_FLAG_DEVICE_FENCES = 2,
+  QUEST_FLAG_KEEP_FIRST_PAGE = 4,
+  QUEST_FLAG_KEEP_NEWEST_PAGE = 8
+};
 
 /* Description of one layer's paged KV cache.  Host struct, passed by pointer;
  * the library reads it during the call only. */
@@ -143,7 +155,7 @@ int quest_append_estimate(const quest_cache* cache, const void* k_new, const voi
 /* Top-K filtering (Section 3.4): for every (b, h) the K_b = min(k_pages, P_b)
  * pages with the largest score among the P_b = ceil(seq_lens[b]/S) valid ones.
  * Scores compare by value (-0 == +0); of equal scores the lower page index is
- * kept.  topk_idx[b][h][0..K_b) receives the chosen logical page ids in
+ * kept.  QUEST_FLAG_KEEP_* in cache->flags force pages into the list (see there).  topk_idx[b][h][0..K_b) receives the chosen logical page ids in
  * ascending order, the rest of the row is set to -1.  k_eff (nullable, int32
  * [batch], device) receives K_b.  Deterministic. */
 int quest_topk(const quest_cache* cache, const float* scores, int32_t k_pages,

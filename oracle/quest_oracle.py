@@ -156,12 +156,17 @@ def estimate(meta, q, page_table, seq_lens, page_size, max_pages=None):
 # Section 3.4: choose the K pages with the highest score
 # --------------------------------------------------------------------------
 
-def topk(scores, seq_lens, page_size, k_pages):
+def topk(scores, seq_lens, page_size, k_pages, keep_first=False, keep_newest=False):
     """Per (b, h): the K_b = min(k_pages, P_b) pages with the largest score.
 
     Ranking: score descending, then page index ascending (so of equal scores
     the lower page wins).  The chosen set is returned in ascending page order,
-    padded with -1.  Returns (topk_idx int32 [B][H][k_pages], k_eff int32 [B])."""
+    padded with -1.  Returns (topk_idx int32 [B][H][k_pages], k_eff int32 [B]).
+
+    keep_first / keep_newest (the paper selects purely by score; these are the
+    two usual additions, kept optional): page 0 / the page of the newest token
+    rank above every score, i.e. they take the first places of the K and the
+    rest is filled by score."""
     B, H, _ = scores.shape
     idx = np.full((B, H, k_pages), -1, np.int32)
     k_eff = np.zeros(B, np.int32)
@@ -172,6 +177,10 @@ def topk(scores, seq_lens, page_size, k_pages):
         for h in range(H):
             s = np.asarray(scores[b, h, :P])
             s = s + 0.0                                      # -0 and +0 rank equal
+            if keep_first:
+                s[0] = np.inf
+            if keep_newest:
+                s[P - 1] = np.inf
             rank = np.lexsort((np.arange(P), -s))            # last key is primary
             idx[b, h, :K] = np.sort(rank[:K])
     return idx, k_eff

@@ -16,6 +16,8 @@ LIB_PATH = os.path.join(_PKG_DIR, "libquest.so")
 QUEST_OK = 0
 QUEST_FLAG_PERSISTENT_STEP = 1
 QUEST_FLAG_DEVICE_FENCES = 2
+QUEST_FLAG_KEEP_FIRST_PAGE = 4
+QUEST_FLAG_KEEP_NEWEST_PAGE = 8
 STATUS_NAMES = {0: "QUEST_OK", -1: "QUEST_ERR_NULL", -2: "QUEST_ERR_SHAPE",
                 -3: "QUEST_ERR_UNSUPPORTED", -4: "QUEST_ERR_WORKSPACE", -5: "QUEST_ERR_HIP"}
 

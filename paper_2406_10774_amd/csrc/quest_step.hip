@@ -54,6 +54,7 @@ struct StepArgs {
   float* part_acc;    // [items * members][D]
   float* part_ml;     // [items * members][2]
   int batch, k_pages, out_is_fp16, force_device_fences;
+  int policy;         // QUEST_FLAG_KEEP_* bits of the cache
   int members;        // M: work-groups per (sequence, head)
   int est_calls;      // blocks of 32 * kIters pages a member scores one after the other
   int list_per_member;  // selected-list positions per member
@@ -157,7 +158,7 @@ __global__ __launch_bounds__(kStepThreads, 4) void step_kernel(const StepArgs a)
     topk_block<kStepThreads, kItems, true>(
         sm.topk, a.est.scores + (size_t)item * max_pages, a.est.seq_lens + b, max_pages, a.k_pages,
         a.topk_idx + (size_t)item * a.k_pages, (h == 0 && a.k_eff != nullptr) ? a.k_eff + b : nullptr,
-        a.est.page_shift
+        a.est.page_shift, a.policy
 #ifdef QUEST_STEP_TRACE
         ,
         a.trace ? a.trace + (size_t)blockIdx.x * 16 + 8 : nullptr
@@ -471,6 +472,7 @@ int launch_decode_step(const quest_cache& c, const void* k_new, const void* v_ne
   a.batch = c.batch;
   a.k_pages = k_pages;
   a.out_is_fp16 = out_is_fp16;
+  a.policy = c.flags;
   a.force_device_fences = force_fences || (c.flags & QUEST_FLAG_DEVICE_FENCES) != 0;
   a.members = p.members;
   a.est_calls = p.est_calls;

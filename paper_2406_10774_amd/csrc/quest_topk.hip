@@ -29,14 +29,15 @@ template <int kThreads, int kItems>
 __global__ __launch_bounds__(kThreads) void topk_kernel(
     const float* __restrict__ scores, const int32_t* __restrict__ seq_lens,
     int32_t* __restrict__ topk_idx, int32_t* __restrict__ k_eff, int num_heads, int max_pages,
-    int k_pages, int page_shift) {
+    int k_pages, int page_shift, int policy) {
   __shared__ TopkShared<kThreads> sm;
   const int h = blockIdx.x;
   const int b = blockIdx.y;
   const size_t bh = (size_t)b * num_heads + h;
   topk_block<kThreads, kItems, false>(sm, scores + bh * max_pages, seq_lens + b, max_pages, k_pages,
                                       topk_idx + bh * k_pages,
-                                      (h == 0 && k_eff != nullptr) ? k_eff + b : nullptr, page_shift);
+                                      (h == 0 && k_eff != nullptr) ? k_eff + b : nullptr, page_shift,
+                                      policy);
 }
 
 // Fallback for rows too long for register-resident keys: keys are re-read from
@@ -45,7 +46,7 @@ constexpr int kBigThreads = 1024;
 __global__ __launch_bounds__(kBigThreads) void topk_big_kernel(
     const float* __restrict__ scores, const int32_t* __restrict__ seq_lens,
     int32_t* __restrict__ topk_idx, int32_t* __restrict__ k_eff, int num_heads, int max_pages,
-    int k_pages, int page_shift) {
+    int k_pages, int page_shift, int policy) {
   constexpr int kWaves = kBigThreads / kWave;
   __shared__ uint32_t hist[256];
   __shared__ int wave_gt[kWaves], wave_eq[kWaves];
@@ -63,6 +64,15 @@ __global__ __launch_bounds__(kBigThreads) void topk_big_kernel(
     for (int i = tid; i < k_pages; i += kBigThreads) out[i] = i < K ? i : -1;
     return;
   }
+  const ForcedPages forced = forced_pages(policy, num_pages);
+  if (forced.count >= K) {
+    if (tid == 0) {
+      out[0] = forced.first ? 0 : num_pages - 1;
+      if (K == 2) out[1] = num_pages - 1;
+    }
+    return;
+  }
+  auto key_of = [&](int i) { return forced.is(i) ? 0xffffffffu : score_key(row[i]); };
   uint32_t prefix = 0;
   int need = K;
   for (int pass = 0; pass < 4; ++pass) {
@@ -71,7 +81,7 @@ __global__ __launch_bounds__(kBigThreads) void topk_big_kernel(
     if (tid < 256) hist[tid] = 0;
     __syncthreads();
     for (int i = tid; i < num_pages; i += kBigThreads) {
-      const uint32_t key = score_key(row[i]);
+      const uint32_t key = key_of(i);
       if ((key & high_mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
     }
     __syncthreads();
@@ -86,7 +96,7 @@ __global__ __launch_bounds__(kBigThreads) void topk_big_kernel(
   const int end = min(begin + items, num_pages);
   int n_gt = 0, n_eq = 0;
   for (int i = begin; i < end; ++i) {
-    const uint32_t key = score_key(row[i]);
+    const uint32_t key = key_of(i);
     n_gt += key > T;
     n_eq += key == T;
   }
@@ -105,7 +115,7 @@ __global__ __launch_bounds__(kBigThreads) void topk_big_kernel(
     }
   }
   for (int i = begin; i < end; ++i) {
-    const uint32_t key = score_key(row[i]);
+    const uint32_t key = key_of(i);
     if (key > T) {
       out[gt_before + min(eq_before, need)] = i;
       ++gt_before;
@@ -121,7 +131,7 @@ int launch_one(const quest_cache& c, const float* scores, int k_pages, int32_t* 
                int32_t* k_eff, hipStream_t s) {
   hipLaunchKernelGGL((topk_kernel<kThreads, kItems>), dim3(c.num_heads, c.batch), dim3(kThreads), 0,
                      s, scores, c.seq_lens, topk_idx, k_eff, c.num_heads, c.max_pages_per_seq,
-                     k_pages, page_shift_of(c.page_size));
+                     k_pages, page_shift_of(c.page_size), c.flags);
   return check_launch("quest_topk");
 }
 
@@ -153,7 +163,7 @@ int launch_topk(const quest_cache& c, const float* scores, int k_pages, int32_t*
 #undef QUEST_TOPK_CASE
   hipLaunchKernelGGL(topk_big_kernel, dim3(c.num_heads, c.batch), dim3(kBigThreads), 0, s, scores,
                      c.seq_lens, topk_idx, k_eff, c.num_heads, c.max_pages_per_seq, k_pages,
-                     page_shift_of(c.page_size));
+                     page_shift_of(c.page_size), c.flags);
   return check_launch("quest_topk");
 }
 

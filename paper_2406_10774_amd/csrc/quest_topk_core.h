@@ -59,6 +59,24 @@ __device__ __forceinline__ BinHit find_bin(const uint32_t* hist, int need, int l
   return r;
 }
 
+// Pages kept whatever their score (quest.h: QUEST_FLAG_KEEP_FIRST_PAGE,
+// QUEST_FLAG_KEEP_NEWEST_PAGE); the page of the newest token is the last valid one.
+struct ForcedPages {
+  bool first, newest;
+  int newest_page, count;
+  __device__ __forceinline__ bool is(int page) const {
+    return (first && page == 0) || (newest && page == newest_page);
+  }
+};
+__device__ __forceinline__ ForcedPages forced_pages(int policy, int num_pages) {
+  ForcedPages f;
+  f.newest_page = num_pages - 1;
+  f.first = (policy & QUEST_FLAG_KEEP_FIRST_PAGE) != 0;
+  f.newest = (policy & QUEST_FLAG_KEEP_NEWEST_PAGE) != 0 && !(f.first && f.newest_page == 0);
+  f.count = (int)f.first + (int)f.newest;
+  return f;
+}
+
 #ifdef QUEST_STEP_TRACE
 #define TOPK_TRACE(slot)                                                        \
   do {                                                                          \
@@ -85,7 +103,7 @@ __device__ __forceinline__ void topk_block(TopkShared<kThreads>& sm, const float
                                            const int32_t* __restrict__ seq_len_ptr, int max_pages,
                                            int k_pages, int32_t* __restrict__ out,
                                            int32_t* __restrict__ k_eff_slot, int page_shift,
-                                           unsigned long long* trace = nullptr) {
+                                           int policy, unsigned long long* trace = nullptr) {
   constexpr int kWaves = kThreads / kWave;
   (void)trace;
   uint32_t(&hist)[4][256] = sm.hist;
@@ -121,6 +139,17 @@ __device__ __forceinline__ void topk_block(TopkShared<kThreads>& sm, const float
     return;
   }
 
+  // Pages that are kept whatever their score rank above every score (key ~0;
+  // finite scores map below 0xff800000) and, like equal scores, by page index.
+  const ForcedPages forced = forced_pages(policy, num_pages);
+  if (forced.count >= K) {  // K is 1 or 2 here: the list is the forced pages, lowest first
+    if (tid == 0) {
+      out[0] = forced.first ? 0 : num_pages - 1;
+      if (K == 2) out[1] = num_pages - 1;
+    }
+    return;
+  }
+
   TOPK_TRACE(4);
   uint32_t key[kItems];
   bool valid[kItems];
@@ -130,7 +159,10 @@ __device__ __forceinline__ void topk_block(TopkShared<kThreads>& sm, const float
   for (int j = 0; j < kItems; ++j) {
     key[j] = score_key(raw[j]);
     valid[j] = base + j < num_pages;
-    differs |= valid[j] && (key[j] & 0xff000000u) != ref_top;
+    if (forced.is(base + j))
+      key[j] = 0xffffffffu;
+    else
+      differs |= valid[j] && (key[j] & 0xff000000u) != ref_top;
   }
   if (__ballot(differs) != 0 && lane == 0) vote = 1;
   __syncthreads();
@@ -141,7 +173,9 @@ __device__ __forceinline__ void topk_block(TopkShared<kThreads>& sm, const float
   // `shift + 8` ... are greater than `prefix`'s, plus `need` of the keys that
   // match `prefix` on the bits decided so far.
   uint32_t prefix = skip_first ? ref_top : 0u;
-  int need = K;
+  // with the first digit skipped the forced keys (top byte 0xff) are never counted:
+  // they are above the threshold for certain
+  int need = skip_first ? K - forced.count : K;
   int decided_shift = skip_first ? 24 : 32;  // bits [decided_shift, 32) of the threshold are known
   bool first_pass = true;
 #pragma unroll

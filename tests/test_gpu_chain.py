@@ -106,7 +106,7 @@ def run_single_launch_steps(w, steps, permute, flags):
     k_pool, v_pool, _ = synth.fill_pools(w, table, N)
     lens = np.array(w.seq_lens, np.int32)
     one = Layer(k_pool, v_pool, table, lens, flags=flags)   # one call
-    ref = Layer(k_pool, v_pool, table, lens)            # separate calls
+    ref = Layer(k_pool, v_pool, table, lens, flags=flags & 12)   # separate calls, same selection policy
     one.build_meta()
     ref.build_meta()
     scale = 1 / math.sqrt(D)
@@ -129,6 +129,11 @@ def run_single_launch_steps(w, steps, permute, flags):
             P = -(-int(cur[b]) // S)
             assert np.array_equal(sc1[b, :, :P].view(np.uint32), sc0[b, :, :P].view(np.uint32)), step
         assert np.array_equal(idx1, idx0) and np.array_equal(keff1, keff0), step
+        if flags & 4:
+            assert (idx1[:, :, 0] == 0).all(), step
+        if flags & 8:
+            for b in range(w.batch):
+                assert ((idx1[b] == (int(cur[b]) - 1) // S).sum(axis=-1) == 1).all(), step
         want, want_lse = O.sparse_decode(k_pool, v_pool, q, table, cur, idx1, scale)
         assert np.abs(out1 - want).max() <= ATTN_TOL, step
         assert np.abs(lse1 - want_lse).max() <= ATTN_TOL, step
@@ -150,6 +155,15 @@ def test_decode_step_ragged_batch(flags):
     w = synth.Workload(92, "ragged-step", 5, 3, (1, 16 * 3 + 7, 16 * 203 + 5, 16 * 64, 16 * 130 + 15),
                        token_budget=16 * 24, planted_per_head=4, decode_steps=24)
     run_single_launch_steps(w, steps=20, permute=True, flags=flags)
+
+
+@pytest.mark.parametrize("flags", [4 | 8, 1 | 4 | 8, 1 | 8])
+def test_decode_step_keeps_forced_pages(flags):
+    """Selection policy flags through the one-call step (three launches and single launch):
+    same list as quest_topk with the same flags; the forced pages are in it."""
+    w = synth.Workload(93, "ragged-policy", 4, 3, (1, 16 * 3 + 7, 16 * 203 + 5, 16 * 64),
+                       token_budget=16 * 24, planted_per_head=4, decode_steps=24)
+    run_single_launch_steps(w, steps=12, permute=True, flags=flags)
 
 
 @pytest.mark.parametrize("flags", [0, 1])

@@ -291,6 +291,32 @@ def test_topk_special_cases():
     assert list(idx[0, 0]) == [1, 2, 6]                          # 7, then the two lowest 5s
 
 
+@pytest.mark.parametrize("keep_first,keep_newest", [(True, False), (False, True), (True, True)])
+def test_topk_forced_pages(keep_first, keep_newest):
+    """Forced pages are in the list whatever their score; the other places go to the best
+    of the remaining pages (built here without the oracle's +inf trick: forced pages out,
+    repeated arg-max over the rest)."""
+    rng = np.random.default_rng(11)
+    S = 16
+    lens = np.array([16 * 29 + 3, 16, 16 * 2], np.int32)         # 30 pages, 1 page, 2 pages
+    sc = np.round(rng.standard_normal((3, 2, 32)) * 4) / 4
+    sc[0, 0, 0] = -50.0                                          # forced pages score worst ...
+    sc[0, 0, 29] = -60.0
+    sc[0, 1, 29] = 50.0                                          # ... or best already
+    for K in (1, 2, 3, 7, 40):
+        idx, keff = O.topk(sc, lens, S, K, keep_first=keep_first, keep_newest=keep_newest)
+        for b in range(3):
+            P = O.num_pages(lens[b], S)
+            forced = ([0] if keep_first else []) + ([P - 1] if keep_newest else [])
+            forced = sorted(set(forced))[:min(K, P)]
+            for h in range(2):
+                rest = [p for p in range(P) if p not in forced]
+                fill = brute_topk(sc[b, h, rest], min(K, P) - len(forced)) if len(forced) < min(K, P) else []
+                want = sorted(forced + [rest[i] for i in fill])
+                assert list(idx[b, h, :keff[b]]) == want, (K, b, h)
+                assert (idx[b, h, keff[b]:] == -1).all()
+
+
 # ------------------------------------------------------------------ attention
 def brute_attention(k_pool, v_pool, q, table, lens, pages_of, scale):
     """Explicit-loop softmax attention over the listed pages, Python floats."""
