@@ -75,3 +75,11 @@ def test_config3_ragged_batch16():
 
 def test_config4_512k_context():
     chain_at_full_size(synth.workload(4), k_pages_list=(256,), steps=1, use_step_call=False)
+
+
+@pytest.mark.parametrize("S", [8, 64])
+def test_config1_shape_other_page_sizes(S):
+    """The benchmark shape (32 heads, 32k context, 2048-token budget) with pages of 8 and of
+    64 tokens, as `bench.py --page-size S` times it."""
+    w = synth.workload(1, page_size=S, decode_steps=4)
+    chain_at_full_size(w, k_pages_list=(w.k_pages,), steps=1, use_step_call=False)
