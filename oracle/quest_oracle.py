@@ -136,19 +136,30 @@ def append_kv(k_pool, v_pool, k_new, v_new, page_table, seq_lens):
 def estimate(meta, q, page_table, seq_lens, page_size, max_pages=None):
     """score[b,h,p] = sum_i max(q_i * m_{p,i}, q_i * M_{p,i}), unscaled, float64.
 
-    Entries p >= P_b are -inf."""
+    Entries p >= P_b are -inf.
+
+    Grouped-query attention (the paper's models have one KV head per query head
+    and it gives no rule for groups; this is the reading used here): when meta
+    has fewer heads than q, query heads [g*G, (g+1)*G) share KV head g, each
+    query head is scored against that head's metadata, and the score of the page
+    for the group is the largest of its heads' scores: still an upper bound of
+    every logit any head of the group can reach in the page.  One row per KV
+    head is returned."""
     B, H, D = q.shape
+    Hkv = meta.shape[0]
+    G = H // Hkv
+    assert G * Hkv == H
     max_pages = page_table.shape[1] if max_pages is None else max_pages
-    scores = np.full((B, H, max_pages), -np.inf, np.float64)
+    scores = np.full((B, Hkv, max_pages), -np.inf, np.float64)
     for b in range(B):
         P = num_pages(seq_lens[b], page_size)
         phys = page_table[b, :P]
         for h in range(H):
             qv = q[b, h].astype(np.float64)                 # [D]
-            m = meta[h, phys, 0, :].astype(np.float64)      # [P][D]
-            M = meta[h, phys, 1, :].astype(np.float64)
+            m = meta[h // G, phys, 0, :].astype(np.float64)      # [P][D]
+            M = meta[h // G, phys, 1, :].astype(np.float64)
             U = np.maximum(qv[None, :] * m, qv[None, :] * M)
-            scores[b, h, :P] = U.sum(axis=1)
+            scores[b, h // G, :P] = np.maximum(scores[b, h // G, :P], U.sum(axis=1))
     return scores
 
 
@@ -195,9 +206,14 @@ def sparse_decode(k_pool, v_pool, q, page_table, seq_lens, topk_idx, sm_scale):
     of the selected pages; topk_idx=None selects every page (dense attention).
 
     Returns (out float64 [B][H][D], lse float64 [B][H]) with
-    lse = log sum_j exp(sm_scale * q.k_j)."""
+    lse = log sum_j exp(sm_scale * q.k_j).
+
+    With fewer KV heads than query heads (see estimate) query head h reads KV
+    head h // G and the page list of that KV head."""
     B, H, D = q.shape
     S = k_pool.shape[2]
+    G = H // k_pool.shape[1]
+    assert G * k_pool.shape[1] == H
     out = np.zeros((B, H, D), np.float64)
     lse = np.zeros((B, H), np.float64)
     for b in range(B):
@@ -207,11 +223,11 @@ def sparse_decode(k_pool, v_pool, q, page_table, seq_lens, topk_idx, sm_scale):
             if topk_idx is None:
                 pages = np.arange(P)
             else:
-                row = np.asarray(topk_idx[b, h])
+                row = np.asarray(topk_idx[b, h // G])
                 pages = row[row >= 0]
             phys = page_table[b, pages]
-            keys = k_pool[phys, h].astype(np.float64).reshape(-1, D)     # [n*S][D]
-            vals = v_pool[phys, h].astype(np.float64).reshape(-1, D)
+            keys = k_pool[phys, h // G].astype(np.float64).reshape(-1, D)     # [n*S][D]
+            vals = v_pool[phys, h // G].astype(np.float64).reshape(-1, D)
             tok = (np.asarray(pages)[:, None] * S + np.arange(S)[None, :]).reshape(-1)
             ok = tok < L
             keys, vals = keys[ok], vals[ok]
