@@ -45,6 +45,9 @@ def parse():
                     help="tokens per page (8, 16, 32, 64) instead of the workload's own; same "
                          "context and token budget (the page-size sweep of the paper's Figure 8)")
     ap.add_argument("--repeats", type=int, default=5, help="graph replays; the median is reported")
+    ap.add_argument("--kv-heads", type=int, default=0,
+                    help="grouped-query attention: KV heads (a divisor of the workload's heads); "
+                         "the workload's heads stay the query heads.  Implies --no-cpu-baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="also time eager (per-call) launches")
     return ap.parse_args()
@@ -66,7 +69,13 @@ def main():
     n_layers = args.layers
     visits = -(-n_total // n_layers)                      # appends per layer buffer
     over = {"page_size": args.page_size} if args.page_size else {}
-    w = synth.workload(args.config, decode_steps=visits + 1, **over)
+    wq = synth.workload(args.config, decode_steps=visits + 1, **over)   # query side
+    Hq = wq.num_heads
+    if args.kv_heads:
+        assert Hq % args.kv_heads == 0, "--kv-heads must divide the number of heads"
+        over["num_heads"] = args.kv_heads
+        args.no_cpu_baseline = True
+    w = synth.workload(args.config, decode_steps=visits + 1, **over)    # KV side
     B, H, S, D, K = w.batch, w.num_heads, w.page_size, w.head_dim, w.k_pages
     scale = 1.0 / math.sqrt(D)
 
@@ -85,7 +94,7 @@ def main():
     lens_steps = np.stack([lens0 + (i // n_layers + 1) for i in range(n_total)]).astype(np.int32)
     lens_dev = torch.from_numpy(lens_steps).to(dev)
     lens0_dev = torch.from_numpy(lens0).to(dev)
-    q_all = dev16(np.stack([synth.gen_query(w, i) for i in range(n_total)]))
+    q_all = dev16(np.stack([synth.gen_query(wq, i) for i in range(n_total)]))
     new_kv = [synth.gen_new_token(w, i) for i in range(n_total)]
     kn_all = dev16(np.stack([k for k, _ in new_kv]))
     vn_all = dev16(np.stack([v for _, v in new_kv]))
@@ -97,12 +106,12 @@ def main():
         meta = torch.zeros((H, N, 2, D), dtype=torch.float16, device=dev)
         Q.quest_build_meta(Q.Cache(kp, vp, meta, pt, lens0_dev))
         layers.append((kp, vp, meta))
-    caches = [Q.Cache(*layers[i % n_layers], pt, lens_dev[i]) for i in range(n_total)]
-    caches_persistent = [Q.Cache(*layers[i % n_layers], pt, lens_dev[i],
+    caches = [Q.Cache(*layers[i % n_layers], pt, lens_dev[i], num_heads=Hq) for i in range(n_total)]
+    caches_persistent = [Q.Cache(*layers[i % n_layers], pt, lens_dev[i], num_heads=Hq,
                                  flags=Q.QUEST_FLAG_PERSISTENT_STEP) for i in range(n_total)]
     scores = torch.zeros((B, H, table.shape[1]), dtype=torch.float32, device=dev)
     idx = torch.zeros((B, H, K), dtype=torch.int32, device=dev)
-    out = torch.zeros((B, H, D), dtype=torch.float32, device=dev)
+    out = torch.zeros((B, Hq, D), dtype=torch.float32, device=dev)
     ws_bytes = max(Q.quest_workspace_bytes(caches[0], K), Q.quest_workspace_bytes(caches[0], 0), 4)
     ws = torch.zeros(ws_bytes // 4, dtype=torch.float32, device=dev)
     ws_step = torch.zeros(max(Q.quest_step_workspace_bytes(caches[0], K), 8) // 4, dtype=torch.int32,
@@ -261,7 +270,8 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(us_step * 1e-3, 6), "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": "f16 in / f32 accumulate", "data": "synthetic",
-        "config": {"workload": w.name, "batch": B, "heads": H, "head_dim": D, "page_size": S,
+        "config": {"workload": w.name, "batch": B, "heads": Hq, "kv_heads": H, "head_dim": D,
+                   "page_size": S,
                    "context": int(lens0.max()), "token_budget": w.token_budget, "k_pages": K,
                    "layer_buffers": n_layers, "launch": "hip-graph replay of the timed steps",
                    "calls_per_step": calls},

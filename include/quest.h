@@ -45,6 +45,16 @@
  *   topk_idx       : int32 [batch][num_heads][k_pages]
  *   out            : fp32 or fp16 [batch][num_heads][head_dim]
  *   lse            : fp32  [batch][num_heads]
+ *
+ * Grouped-query attention (num_kv_heads = Hkv < num_heads = H, G = H / Hkv; the
+ * paper's models have G == 1 and it gives no rule for groups, this is the
+ * library's reading): query heads [g G, (g + 1) G) share KV head g.  k_pool,
+ * v_pool, meta, k_new, v_new, scores and topk_idx then have Hkv where the
+ * layouts above say num_heads; q, out and lse keep H.  A page's score for a KV
+ * head is the largest of the scores of the group's query heads (each computed
+ * as in quest_estimate against that KV head's metadata): still an upper bound
+ * of every attention logit any head of the group can reach in the page.  One
+ * page list per KV head; every query head of the group attends over it.
  */
 #ifndef QUEST_H_
 #define QUEST_H_
@@ -104,6 +114,8 @@ typedef struct quest_cache {
   void* meta;                 /* device, fp16                                */
   const int32_t* page_table;  /* device                                      */
   const int32_t* seq_lens;    /* device                                      */
+  int32_t num_kv_heads;       /* 0 or num_heads: one KV head per query head;
+                                 else a divisor of num_heads (see below)     */
 } quest_cache;
 
 /* Bytes of device workspace quest_sparse_decode needs for this cache and

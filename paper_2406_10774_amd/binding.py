@@ -40,6 +40,7 @@ class quest_cache(ctypes.Structure):
         ("num_phys_pages", ctypes.c_int64),
         ("k_pool", ctypes.c_void_p), ("v_pool", ctypes.c_void_p), ("meta", ctypes.c_void_p),
         ("page_table", ctypes.c_void_p), ("seq_lens", ctypes.c_void_p),
+        ("num_kv_heads", ctypes.c_int32),
     ]
 
 
@@ -97,15 +98,19 @@ class Cache:
 
     Holds references to the caller's torch tensors so they outlive the calls."""
 
-    def __init__(self, k_pool, v_pool, meta, page_table, seq_lens, flags=0):
-        N, H, S, D = k_pool.shape
+    def __init__(self, k_pool, v_pool, meta, page_table, seq_lens, flags=0, num_heads=None):
+        """num_heads: query heads, if more than the KV heads of the pools (grouped-query
+        attention); default: one KV head per query head."""
+        N, Hkv, S, D = k_pool.shape
+        H = Hkv if num_heads is None else int(num_heads)
         self.k_pool, self.v_pool, self.meta = k_pool, v_pool, meta
         self.page_table, self.seq_lens = page_table, seq_lens
         self.c = quest_cache(
             batch=page_table.shape[0], num_heads=H, head_dim=D, page_size=S,
             max_pages_per_seq=page_table.shape[1], flags=int(flags), num_phys_pages=N,
             k_pool=k_pool.data_ptr(), v_pool=v_pool.data_ptr() if v_pool is not None else None,
-            meta=meta.data_ptr(), page_table=page_table.data_ptr(), seq_lens=seq_lens.data_ptr())
+            meta=meta.data_ptr(), page_table=page_table.data_ptr(), seq_lens=seq_lens.data_ptr(),
+            num_kv_heads=0 if H == Hkv else Hkv)
 
     @property
     def ref(self):

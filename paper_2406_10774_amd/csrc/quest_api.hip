@@ -49,6 +49,11 @@ int check_cache(const quest_cache* c, const char* who) {
     set_error("%s: max_pages_per_seq * page_size exceeds the int32 range of seq_lens", who);
     return QUEST_ERR_SHAPE;
   }
+  if (c->num_kv_heads < 0 || (c->num_kv_heads > 0 && c->num_heads % c->num_kv_heads != 0)) {
+    set_error("%s: num_kv_heads must be 0 or a divisor of num_heads (got %d, %d)", who,
+              c->num_kv_heads, c->num_heads);
+    return QUEST_ERR_SHAPE;
+  }
   if (c->page_table == nullptr || c->seq_lens == nullptr) {
     set_error("%s: page_table and seq_lens must not be NULL", who);
     return QUEST_ERR_NULL;

@@ -32,6 +32,10 @@ constexpr int kMetaBytes = 2 * kHeadDim * 2;
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef short short2_t __attribute__((ext_vector_type(2)));
 
+// KV heads and query heads per KV head of a cache (grouped-query attention).
+inline int kv_heads(const quest_cache& c) { return c.num_kv_heads > 0 ? c.num_kv_heads : c.num_heads; }
+inline int group_size(const quest_cache& c) { return c.num_heads / kv_heads(c); }
+
 // ---------------------------------------------------------------- host side
 void set_error(const char* fmt, ...);
 int check_cache(const quest_cache* c, const char* who);

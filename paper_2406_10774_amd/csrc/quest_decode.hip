@@ -60,6 +60,7 @@ struct DecodeArgs {
   int list_len;             // entries of the page list the splits divide: k_pages, or max_pages
   int per_split;            // ceil(list_len / splits)
   int force_device_fences;  // debug: take the cross-die exchange path
+  int kv_heads, group;      // KV heads; query heads per KV head (num_heads = kv_heads * group)
   int page_shift;           // log2(tokens per page)
   int unit_shift;           // log2(streaming units per page): 0 up to 16 tokens, 1 for 32, 2 for 64
   float scale_log2;         // sm_scale * log2(e)
@@ -106,7 +107,9 @@ __global__ __launch_bounds__(kDecThreads) void decode_split_kernel(const DecodeA
   const int begin = split * a.per_split;
   const int end = min(a.list_len, begin + a.per_split);
   const int iters = (a.per_split + kDecWaves - 1) / kDecWaves;
-  const int32_t* idx_row = a.topk_idx ? a.topk_idx + bh * a.k_pages : nullptr;
+  const int hk = h / a.group;  // the KV head this query head reads, and whose page list it uses
+  const int32_t* idx_row =
+      a.topk_idx ? a.topk_idx + ((size_t)b * a.kv_heads + hk) * a.k_pages : nullptr;
   const int32_t* pt = a.page_table + (size_t)b * a.max_pages;
 
   const int seq_len = a.seq_lens[b];
@@ -136,7 +139,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_split_kernel(const DecodeA
     if (__builtin_amdgcn_readlane(ph_v, 0) >= 0) DEC_TRACE(1);
 
 #define QUEST_LOAD_UNIT(regs, i)                                                               \
-  load_unit<kLoads>(regs, a.k_pool, a.v_pool, a.num_heads, h, seq_len, __builtin_amdgcn_readlane(lp_v, i), \
+  load_unit<kLoads>(regs, a.k_pool, a.v_pool, a.kv_heads, hk, seq_len, __builtin_amdgcn_readlane(lp_v, i), \
                     __builtin_amdgcn_readlane(ph_v, i), __builtin_amdgcn_readlane(un_v, i),    \
                     a.page_shift, lane)
     PageRegsT<kLoads> ra, rb;
@@ -315,6 +318,8 @@ int launch_sparse_decode(const quest_cache& c, const void* q, const int32_t* top
   a.topk_idx = topk_idx;
   a.batch = c.batch;
   a.num_heads = c.num_heads;
+  a.kv_heads = kv_heads(c);
+  a.group = group_size(c);
   a.max_pages = c.max_pages_per_seq;
   a.k_pages = topk_idx ? k_pages : 0;
   const SplitPlan p = plan_splits(c, a.k_pages);

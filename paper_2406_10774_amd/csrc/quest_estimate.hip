@@ -37,7 +37,8 @@ EstimateArgs make_args(const quest_cache& c, const void* q, float* scores) {
   a.page_table = c.page_table;
   a.seq_lens = c.seq_lens;
   a.scores = scores;
-  a.num_heads = c.num_heads;
+  a.num_heads = kv_heads(c);
+  a.group = group_size(c);
   a.max_pages = c.max_pages_per_seq;
   a.num_phys_pages = c.num_phys_pages;
   a.page_shift = page_shift_of(c.page_size);
@@ -49,7 +50,7 @@ EstimateArgs make_args(const quest_cache& c, const void* q, float* scores) {
 }  // namespace
 
 int launch_estimate(const quest_cache& c, const void* q, float* scores, hipStream_t s) {
-  dim3 grid((c.max_pages_per_seq + kEstPagesPerGroup - 1) / kEstPagesPerGroup, c.num_heads, c.batch);
+  dim3 grid((c.max_pages_per_seq + kEstPagesPerGroup - 1) / kEstPagesPerGroup, kv_heads(c), c.batch);
   hipLaunchKernelGGL(estimate_kernel<false>, grid, dim3(kEstWaves * kWave), 0, s,
                      make_args(c, q, scores));
   return check_launch("quest_estimate");
@@ -57,7 +58,7 @@ int launch_estimate(const quest_cache& c, const void* q, float* scores, hipStrea
 
 int launch_append_estimate(const quest_cache& c, const void* k_new, const void* v_new,
                            int k_pool_write, const void* q, float* scores, hipStream_t s) {
-  dim3 grid((c.max_pages_per_seq + kEstPagesPerGroup - 1) / kEstPagesPerGroup, c.num_heads, c.batch);
+  dim3 grid((c.max_pages_per_seq + kEstPagesPerGroup - 1) / kEstPagesPerGroup, kv_heads(c), c.batch);
   EstimateArgs a = make_args(c, q, scores);
   a.k_new = (const char*)k_new;
   a.v_new = (const char*)v_new;

@@ -21,7 +21,8 @@ struct EstimateArgs {
   const int32_t* page_table;
   const int32_t* seq_lens;
   float* scores;
-  int num_heads, max_pages;
+  int num_heads, max_pages;  // num_heads: KV heads (rows of meta, pools, scores)
+  int group;                 // query heads per KV head: q has num_heads * group heads
   int64_t num_phys_pages;
   const char* k_new;  // kAppend only
   const char* v_new;
@@ -62,7 +63,8 @@ __device__ __forceinline__ void estimate_wave(const EstimateArgs& a, int b, int 
     const int p = base + kIters * grp + it;
     phys[it] = p < max_pages ? pt[p] : 0;
   }
-  const uint4 qv = ld16(q + bh * (kHeadDim * 2) + c * 16);
+  const int group = a.group;
+  const uint4 qv = ld16(q + bh * group * (kHeadDim * 2) + c * 16);  // first query head of the group
   const int page_shift = a.page_shift;
   const int num_pages = (seq_len + (1 << page_shift) - 1) >> page_shift;
   if (base >= num_pages) return;
@@ -111,24 +113,33 @@ __device__ __forceinline__ void estimate_wave(const EstimateArgs& a, int b, int 
     }
   }
 
-  // per half: 0xffff where q is negative (min row wins), 0 elsewhere (max row wins)
-  uint4 neg;
-  neg.x = __builtin_bit_cast(uint32_t, __builtin_bit_cast(short2_t, qv.x) >> 15);
-  neg.y = __builtin_bit_cast(uint32_t, __builtin_bit_cast(short2_t, qv.y) >> 15);
-  neg.z = __builtin_bit_cast(uint32_t, __builtin_bit_cast(short2_t, qv.z) >> 15);
-  neg.w = __builtin_bit_cast(uint32_t, __builtin_bit_cast(short2_t, qv.w) >> 15);
-
-  float keep = 0.f;
+  // One query head against the pages this wave holds: lane c of a row keeps the
+  // score of the row's c-th page.
+  auto score_pages = [&](const uint4 qh) {
+    // per half: 0xffff where q is negative (min row wins), 0 elsewhere (max row wins)
+    uint4 neg;
+    neg.x = __builtin_bit_cast(uint32_t, __builtin_bit_cast(short2_t, qh.x) >> 15);
+    neg.y = __builtin_bit_cast(uint32_t, __builtin_bit_cast(short2_t, qh.y) >> 15);
+    neg.z = __builtin_bit_cast(uint32_t, __builtin_bit_cast(short2_t, qh.z) >> 15);
+    neg.w = __builtin_bit_cast(uint32_t, __builtin_bit_cast(short2_t, qh.w) >> 15);
+    float mine = 0.f;
 #pragma unroll
-  for (int it = 0; it < kIters; ++it) {
-    uint4 sel;
-    sel.x = (mn[it].x & neg.x) | (mx[it].x & ~neg.x);
-    sel.y = (mn[it].y & neg.y) | (mx[it].y & ~neg.y);
-    sel.z = (mn[it].z & neg.z) | (mx[it].z & ~neg.z);
-    sel.w = (mn[it].w & neg.w) | (mx[it].w & ~neg.w);
-    const float s = row16_sum(dot8(qv, sel, 0.f));
-    if (c == it) keep = s;
-  }
+    for (int it = 0; it < kIters; ++it) {
+      uint4 sel;
+      sel.x = (mn[it].x & neg.x) | (mx[it].x & ~neg.x);
+      sel.y = (mn[it].y & neg.y) | (mx[it].y & ~neg.y);
+      sel.z = (mn[it].z & neg.z) | (mx[it].z & ~neg.z);
+      sel.w = (mn[it].w & neg.w) | (mx[it].w & ~neg.w);
+      const float s = row16_sum(dot8(qh, sel, 0.f));
+      if (c == it) mine = s;
+    }
+    return mine;
+  };
+  // The page's score for the KV head: the largest of its query heads' scores
+  // (one query head per KV head in the paper's models: no further round).
+  float keep = score_pages(qv);
+  for (int g = 1; g < group; ++g)
+    keep = fmaxf(keep, score_pages(ld16(q + (bh * group + g) * (kHeadDim * 2) + c * 16)));
   // lanes c < 4 of each row hold 4 consecutive pages: 16 consecutive floats per wave
   const int p = base + kIters * grp + c;
   if (c < kIters && p < num_pages) scores[bh * max_pages + p] = keep;

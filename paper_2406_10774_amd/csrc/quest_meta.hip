@@ -118,9 +118,9 @@ __global__ __launch_bounds__(256) void append_meta_kernel(
 template <int kS>
 int launch_build_meta_for(const quest_cache& c, hipStream_t s) {
   constexpr int kPagesPerGroup = kBuildWaves * (kBuildLoads / (kS / 4));
-  dim3 grid((c.max_pages_per_seq + kPagesPerGroup - 1) / kPagesPerGroup, c.num_heads, c.batch);
+  dim3 grid((c.max_pages_per_seq + kPagesPerGroup - 1) / kPagesPerGroup, kv_heads(c), c.batch);
   hipLaunchKernelGGL(build_meta_kernel<kS>, grid, dim3(kBuildWaves * kWave), 0, s,
-                     (const char*)c.k_pool, (char*)c.meta, c.page_table, c.seq_lens, c.num_heads,
+                     (const char*)c.k_pool, (char*)c.meta, c.page_table, c.seq_lens, kv_heads(c),
                      c.max_pages_per_seq, c.num_phys_pages);
   return check_launch("quest_build_meta");
 }
@@ -136,10 +136,10 @@ int launch_build_meta(const quest_cache& c, hipStream_t s) {
 
 int launch_append_meta(const quest_cache& c, const void* k_new, const void* v_new, int k_pool_write,
                        hipStream_t s) {
-  const int threads = c.batch * c.num_heads * 16;
+  const int threads = c.batch * kv_heads(c) * 16;
   hipLaunchKernelGGL(append_meta_kernel, dim3((threads + 255) / 256), dim3(256), 0, s,
                      (char*)c.k_pool, (char*)c.v_pool, (char*)c.meta, c.page_table, c.seq_lens,
-                     (const char*)k_new, (const char*)v_new, c.batch, c.num_heads,
+                     (const char*)k_new, (const char*)v_new, c.batch, kv_heads(c),
                      c.max_pages_per_seq, k_pool_write, c.num_phys_pages,
                      page_shift_of(c.page_size));
   return check_launch("quest_append_meta");

@@ -357,8 +357,10 @@ StepPlan plan_step(const quest_cache& c, int k_pages) {
   StepPlan p = {};
   const long items = (long)c.batch * c.num_heads;
   const int cap = resident_capacity();
-  // opt-in, 16-token pages, rows within the in-register selection, every team resident at once
-  p.fused = (c.flags & QUEST_FLAG_PERSISTENT_STEP) && c.page_size == kPageSize && cap > 0 &&
+  // opt-in, 16-token pages, one KV head per query head, rows within the in-register selection,
+  // every team resident at once
+  p.fused = (c.flags & QUEST_FLAG_PERSISTENT_STEP) && c.page_size == kPageSize &&
+            group_size(c) == 1 && cap > 0 &&
             items <= cap && c.max_pages_per_seq <= kStepThreads * 16;
   if (!p.fused) return p;
   const int mp = c.max_pages_per_seq;
@@ -453,6 +455,7 @@ int launch_decode_step(const quest_cache& c, const void* k_new, const void* v_ne
   a.est.max_pages = c.max_pages_per_seq;
   a.est.num_phys_pages = c.num_phys_pages;
   a.est.page_shift = page_shift_of(c.page_size);
+  a.est.group = 1;
   a.est.k_new = (const char*)k_new;
   a.est.v_new = (const char*)v_new;
   a.est.k_pool = (char*)c.k_pool;

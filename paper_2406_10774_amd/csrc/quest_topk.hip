@@ -129,8 +129,8 @@ __global__ __launch_bounds__(kBigThreads) void topk_big_kernel(
 template <int kThreads, int kItems>
 int launch_one(const quest_cache& c, const float* scores, int k_pages, int32_t* topk_idx,
                int32_t* k_eff, hipStream_t s) {
-  hipLaunchKernelGGL((topk_kernel<kThreads, kItems>), dim3(c.num_heads, c.batch), dim3(kThreads), 0,
-                     s, scores, c.seq_lens, topk_idx, k_eff, c.num_heads, c.max_pages_per_seq,
+  hipLaunchKernelGGL((topk_kernel<kThreads, kItems>), dim3(kv_heads(c), c.batch), dim3(kThreads), 0,
+                     s, scores, c.seq_lens, topk_idx, k_eff, kv_heads(c), c.max_pages_per_seq,
                      k_pages, page_shift_of(c.page_size), c.flags);
   return check_launch("quest_topk");
 }
@@ -161,8 +161,8 @@ int launch_topk(const quest_cache& c, const float* scores, int k_pages, int32_t*
   QUEST_TOPK_CASE(1024, 48);
   if (mp < 65536) return launch_one<1024, 64>(c, scores, k_pages, topk_idx, k_eff, s);
 #undef QUEST_TOPK_CASE
-  hipLaunchKernelGGL(topk_big_kernel, dim3(c.num_heads, c.batch), dim3(kBigThreads), 0, s, scores,
-                     c.seq_lens, topk_idx, k_eff, c.num_heads, c.max_pages_per_seq, k_pages,
+  hipLaunchKernelGGL(topk_big_kernel, dim3(kv_heads(c), c.batch), dim3(kBigThreads), 0, s, scores,
+                     c.seq_lens, topk_idx, k_eff, kv_heads(c), c.max_pages_per_seq, k_pages,
                      page_shift_of(c.page_size), c.flags);
   return check_launch("quest_topk");
 }

@@ -11,12 +11,13 @@ class Layer:
     """Device copy of one layer's paged KV cache plus the buffers of a decode step."""
 
     def __init__(self, k_pool, v_pool, page_table, seq_lens, meta_fill=None, device="cuda:0",
-                 flags=0):
+                 flags=0, num_q_heads=None):
         import torch
         self.torch = torch
         self.dev = device
         N, H, S, D = k_pool.shape
-        self.N, self.H, self.S, self.D = N, H, S, D
+        self.N, self.H, self.S, self.D = N, H, S, D          # H: KV heads
+        self.Hq = H if num_q_heads is None else num_q_heads   # query heads (grouped-query attention)
         self.B, self.max_pages = page_table.shape
         self.k_pool = self._to_dev(k_pool)
         self.v_pool = self._to_dev(v_pool)
@@ -26,7 +27,7 @@ class Layer:
         self.page_table = torch.from_numpy(np.ascontiguousarray(page_table)).to(device)
         self.seq_lens = torch.from_numpy(np.asarray(seq_lens, np.int32)).to(device)
         self.cache = Q.Cache(self.k_pool, self.v_pool, self.meta, self.page_table, self.seq_lens,
-                             flags=flags)
+                             flags=flags, num_heads=self.Hq)
         self.scores = torch.full((self.B, H, self.max_pages), float("nan"), dtype=torch.float32,
                                  device=device)
 
@@ -76,9 +77,9 @@ class Layer:
             idx = torch.from_numpy(np.ascontiguousarray(topk_idx, dtype=np.int32)).to(self.dev)
         ws_bytes = Q.quest_workspace_bytes(self.cache, k_pages if idx is not None else 0)
         ws = torch.zeros(max(ws_bytes, 4) // 4, dtype=torch.float32, device=self.dev)
-        out = torch.full((self.B, self.H, self.D), float("nan"),
+        out = torch.full((self.B, self.Hq, self.D), float("nan"),
                          dtype=torch.float16 if fp16_out else torch.float32, device=self.dev)
-        lse = torch.full((self.B, self.H), float("nan"), dtype=torch.float32, device=self.dev) \
+        lse = torch.full((self.B, self.Hq), float("nan"), dtype=torch.float32, device=self.dev) \
             if want_lse else None
         Q.quest_sparse_decode(self.cache, self.half(q), idx, k_pages, sm_scale, out, lse, ws)
         torch.cuda.synchronize()
@@ -95,8 +96,8 @@ class Layer:
             self._step_ws_k = k_pages
         idx = torch.full((self.B, self.H, k_pages), -7, dtype=torch.int32, device=self.dev)
         keff = torch.full((self.B,), -7, dtype=torch.int32, device=self.dev)
-        out = torch.full((self.B, self.H, self.D), float("nan"), dtype=torch.float32, device=self.dev)
-        lse = torch.full((self.B, self.H), float("nan"), dtype=torch.float32, device=self.dev)
+        out = torch.full((self.B, self.Hq, self.D), float("nan"), dtype=torch.float32, device=self.dev)
+        lse = torch.full((self.B, self.Hq), float("nan"), dtype=torch.float32, device=self.dev)
         self.scores.fill_(float("nan"))
         Q.quest_decode_step(self.cache, None if k_new is None else self.half(k_new),
                             None if v_new is None else self.half(v_new), write, self.half(q),
@@ -106,7 +107,7 @@ class Layer:
         nbytes = Q.quest_step_workspace_bytes(self.cache, k_pages)
         status = int(self._step_ws[(nbytes - 256) // 4].item())
         assert status == 0, f"decode step left work undone (status {status})"
-        assert int(self._step_ws[:64 * self.B * self.H].abs().max().item()) == 0   # counters re-armed
+        assert int(self._step_ws[:64 * self.B * self.Hq].abs().max().item()) == 0   # counters re-armed
         return (self.scores.cpu().numpy(), idx.cpu().numpy(), keff.cpu().numpy(),
                 out.cpu().numpy(), lse.cpu().numpy())
 
@@ -119,15 +120,19 @@ def score_tolerance(meta, q, page_table, seq_lens, S):
     summed in fp32 in any order differ from the exact sum by at most
     (n-1) * 2^-24 * sum|U_i| (n = 128); the DPP tree is far inside that."""
     B, H, D = q.shape
-    tol = np.zeros((B, H, page_table.shape[1]))
+    Hkv = meta.shape[0]
+    G = H // Hkv            # query heads per KV head: the group's score is the largest of its
+    #                         heads' scores, so its error is at most the largest of their bounds
+    tol = np.zeros((B, Hkv, page_table.shape[1]))
     for b in range(B):
         P = -(-int(seq_lens[b]) // S)
         phys = page_table[b, :P]
         for h in range(H):
             qv = q[b, h].astype(np.float64)
-            a = np.abs(qv[None] * meta[h, phys, 0].astype(np.float64))
-            c = np.abs(qv[None] * meta[h, phys, 1].astype(np.float64))
-            tol[b, h, :P] = np.maximum(a, c).sum(-1) * (D * 2.0 ** -24) + 1e-30
+            a = np.abs(qv[None] * meta[h // G, phys, 0].astype(np.float64))
+            c = np.abs(qv[None] * meta[h // G, phys, 1].astype(np.float64))
+            t = np.maximum(a, c).sum(-1) * (D * 2.0 ** -24) + 1e-30
+            tol[b, h // G, :P] = np.maximum(tol[b, h // G, :P], t)
     return tol
 
 

@@ -50,7 +50,7 @@ def test_workspace_bytes_is_pure_and_consistent():
 @pytest.mark.parametrize("kw,status", [
     (dict(head_dim=64), -3), (dict(page_size=24), -3), (dict(page_size=128), -3), (dict(batch=0), -2),
     (dict(num_heads=70000), -2), (dict(page_table=None), -1), (dict(seq_lens=None), -1),
-    (dict(max_pages_per_seq=0), -2),
+    (dict(max_pages_per_seq=0), -2), (dict(num_kv_heads=5), -2), (dict(num_kv_heads=-1), -2),
 ])
 def test_bad_cache_is_rejected_on_the_host(kw, status):
     lib = binding.load()

@@ -19,13 +19,17 @@ def torch_index(layer, ids):
     return layer.torch.from_numpy(np.asarray(ids, np.int64)).to(layer.dev)
 
 
-def run_chain(w, steps, permute):
+def run_chain(w, steps, permute, group=1):
+    """group > 1: grouped-query attention, w describes the KV heads and every KV head
+    serves `group` query heads."""
+    import dataclasses
     from gpu_util import Layer, check_selection, score_tolerance
     S, D = w.page_size, w.head_dim
+    wq = dataclasses.replace(w, num_heads=w.num_heads * group)    # generator of the queries
     table, N = synth.make_page_table(w, permute=permute)
     k_pool, v_pool, q0 = synth.fill_pools(w, table, N)
     lens = np.array(w.seq_lens, np.int32)
-    layer = Layer(k_pool, v_pool, table, lens)
+    layer = Layer(k_pool, v_pool, table, lens, num_q_heads=wq.num_heads)
     scale = 1 / math.sqrt(D)
 
     meta = O.build_meta(k_pool, table, lens)
@@ -36,7 +40,7 @@ def run_chain(w, steps, permute):
     cur = lens.copy()
     near_ties = 0
     for step in range(steps):
-        q = synth.gen_query(w, step)
+        q = synth.gen_query(wq, step)
         fused = step % 2 == 1                          # odd steps: one launch for append + estimate
         if step > 0:                                   # append one token, then attend
             k_new, v_new = synth.gen_new_token(w, step)
@@ -76,7 +80,7 @@ def run_chain(w, steps, permute):
         assert np.array_equal(got_v[i, :, :n_last[b]].view(np.uint16),
                               v_pool[last[b], :, :n_last[b]].view(np.uint16))
     # dense path on the same buffers
-    q = synth.gen_query(w, 0)
+    q = synth.gen_query(wq, 0)
     want, want_lse = O.sparse_decode(k_pool, v_pool, q, table, cur, None, scale)
     got, lse = layer.decode(q, None, 0)
     assert np.abs(got - want).max() <= ATTN_TOL
@@ -97,22 +101,26 @@ def test_config1_full_size_chain_shuffled_pages():
     run_chain(synth.workload(1), steps=18, permute=True)   # step 17 opens nothing new, 1..16 fill page 2048
 
 
-def run_single_launch_steps(w, steps, permute, flags):
+def run_single_launch_steps(w, steps, permute, flags, group=1):
     """quest_decode_step against the separate calls (bit-equal metadata, pools, scores
-    and page list) and against the oracle (attention within tolerance)."""
+    and page list) and against the oracle (attention within tolerance).  group > 1:
+    grouped-query attention, w describes the KV heads."""
+    import dataclasses
     from gpu_util import Layer
     S, D = w.page_size, w.head_dim
+    wq = dataclasses.replace(w, num_heads=w.num_heads * group)
     table, N = synth.make_page_table(w, permute=permute)
     k_pool, v_pool, _ = synth.fill_pools(w, table, N)
     lens = np.array(w.seq_lens, np.int32)
-    one = Layer(k_pool, v_pool, table, lens, flags=flags)   # one call
-    ref = Layer(k_pool, v_pool, table, lens, flags=flags & 12)   # separate calls, same selection policy
+    one = Layer(k_pool, v_pool, table, lens, flags=flags, num_q_heads=wq.num_heads)   # one call
+    ref = Layer(k_pool, v_pool, table, lens, flags=flags & 12,
+                num_q_heads=wq.num_heads)               # separate calls, same selection policy
     one.build_meta()
     ref.build_meta()
     scale = 1 / math.sqrt(D)
     cur = lens.copy()
     for step in range(steps):
-        q = synth.gen_query(w, step)
+        q = synth.gen_query(wq, step)
         k_new, v_new = synth.gen_new_token(w, step)
         append = step % 3 != 2                          # every third step: no new token
         if append:
