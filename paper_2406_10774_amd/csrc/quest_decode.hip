@@ -30,6 +30,7 @@ namespace quest {
 
 namespace {
 
+constexpr int kComputeUnits = 256;  // MI355X; only used to decide how finely to split
 constexpr int kDecWaves = 4;
 constexpr int kDecThreads = kDecWaves * kWave;
 
@@ -77,20 +78,26 @@ struct DecodeArgs {
 // The placement is verified at run time (see quest_team.h): if the splits of a
 // head do not all run on one die, the exchange falls back to device-scope
 // release/acquire fences: slow, still correct.
-template <int kLoads>  // wave-wide 16-byte loads per unit of keys (and of values): 4, or 2 for 8-token pages
+// kLoads: wave-wide 16-byte loads per unit of keys (and of values): 4, or 2 for 8-token
+// pages.  kG: query heads served by one work-group (they share the KV head, so a page is
+// loaded once for all of them): 1 unless grouped-query attention; a group of G heads is
+// served by G / kG work-groups per split.
+template <int kLoads, int kG>
 __global__ __launch_bounds__(kDecThreads) void decode_split_kernel(const DecodeArgs a) {
-  __shared__ float sm_acc[kDecWaves][kHeadDim];
-  __shared__ float sm_m[kDecWaves], sm_l[kDecWaves];
+  __shared__ float sm_acc[kDecWaves][kG][kHeadDim];
+  __shared__ float sm_m[kDecWaves][kG], sm_l[kDecWaves][kG];
   __shared__ uint32_t sm_before[2];
 
   const int slot = blockIdx.x & 7;
   const int rank = blockIdx.x >> 3;
   const int split = rank % a.splits;
-  const int bh_i = (rank / a.splits) * 8 + slot;
-  if (bh_i >= a.batch * a.num_heads) return;
-  const int b = bh_i / a.num_heads;
-  const int h = bh_i - b * a.num_heads;
-  const size_t bh = bh_i;
+  const int item = (rank / a.splits) * 8 + slot;  // (sequence, KV head, kG query heads of its group)
+  const int subs = a.group / kG;
+  if (item >= a.batch * a.kv_heads * subs) return;
+  const int b = item / (a.kv_heads * subs);
+  const int hk = (item - b * a.kv_heads * subs) / subs;  // the KV head: its pages, its page list
+  const int h = hk * a.group + (item % subs) * kG;        // first query head served here
+  const size_t bh = (size_t)b * a.num_heads + h;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = lane_id();
   const int grp = lane >> 4;
@@ -107,19 +114,21 @@ __global__ __launch_bounds__(kDecThreads) void decode_split_kernel(const DecodeA
   const int begin = split * a.per_split;
   const int end = min(a.list_len, begin + a.per_split);
   const int iters = (a.per_split + kDecWaves - 1) / kDecWaves;
-  const int hk = h / a.group;  // the KV head this query head reads, and whose page list it uses
   const int32_t* idx_row =
       a.topk_idx ? a.topk_idx + ((size_t)b * a.kv_heads + hk) * a.k_pages : nullptr;
   const int32_t* pt = a.page_table + (size_t)b * a.max_pages;
 
   const int seq_len = a.seq_lens[b];
-  const uint4 qv = ld16(a.q + bh * (kHeadDim * 2) + c * 16);
-
-  Softmax st;
-  st.m = kNegBig;
-  st.l = 0.f;
+  uint4 qv[kG];
+  Softmax st[kG];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) st.acc[j] = 0.f;
+  for (int g = 0; g < kG; ++g) {
+    qv[g] = ld16(a.q + (bh + g) * (kHeadDim * 2) + c * 16);
+    st[g].m = kNegBig;
+    st[g].l = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) st[g].acc[j] = 0.f;
+  }
 
   // A page is streamed as 1 << unit_shift units of up to 16 tokens; lane i of a
   // round holds unit i of this wave: list entry i >> unit_shift, unit i & mask.
@@ -142,6 +151,13 @@ __global__ __launch_bounds__(kDecThreads) void decode_split_kernel(const DecodeA
   load_unit<kLoads>(regs, a.k_pool, a.v_pool, a.kv_heads, hk, seq_len, __builtin_amdgcn_readlane(lp_v, i), \
                     __builtin_amdgcn_readlane(ph_v, i), __builtin_amdgcn_readlane(un_v, i),    \
                     a.page_shift, lane)
+#define QUEST_FOLD(regs)                                  \
+  do {                                                    \
+    if (kG == 1)                                          \
+      fold_page(st[0], regs, qv[0], a.scale_log2, grp);   \
+    else                                                  \
+      fold_group(st, regs, qv, a.scale_log2, grp);        \
+  } while (0)
     PageRegsT<kLoads> ra, rb;
     int j = 0;
     int lp = __builtin_amdgcn_readlane(lp_v, 0);
@@ -150,15 +166,16 @@ __global__ __launch_bounds__(kDecThreads) void decode_split_kernel(const DecodeA
       int lp_b = -1;
       if (j + 1 < n_here) lp_b = __builtin_amdgcn_readlane(lp_v, j + 1);
       if (lp_b >= 0) QUEST_LOAD_UNIT(rb, j + 1);
-      fold_page(st, ra, qv, a.scale_log2, grp);
+      QUEST_FOLD(ra);
       if (lp_b < 0) break;
       j += 2;
       lp = -1;
       if (j < n_here) lp = __builtin_amdgcn_readlane(lp_v, j);
       if (lp >= 0) QUEST_LOAD_UNIT(ra, j);
-      fold_page(st, rb, qv, a.scale_log2, grp);
+      QUEST_FOLD(rb);
     }
 #undef QUEST_LOAD_UNIT
+#undef QUEST_FOLD
   }
 
   // the four DPP rows of the wave, then the four waves of the group
@@ -167,43 +184,50 @@ __global__ __launch_bounds__(kDecThreads) void decode_split_kernel(const DecodeA
   // now, the answer is needed only when this split publishes
   uint64_t seen = 0;
   if (a.splits > 1 && threadIdx.x == 0) seen = team_load(team_word);
-  merge_lanes(st, 16);
-  merge_lanes(st, 32);
-  if (lane < 16) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) sm_acc[wave][c * 8 + j] = st.acc[j];
-    if (lane == 0) {
-      sm_m[wave] = st.m;
-      sm_l[wave] = st.l;
+  for (int g = 0; g < kG; ++g) {
+    merge_lanes(st[g], 16);
+    merge_lanes(st[g], 32);
+    if (lane < 16) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) sm_acc[wave][g][c * 8 + j] = st[g].acc[j];
+      if (lane == 0) {
+        sm_m[wave][g] = st[g].m;
+        sm_l[wave][g] = st[g].l;
+      }
     }
   }
   __syncthreads();
   const int t = threadIdx.x;
-  float m_tot = sm_m[0];
+  // ---- this split's result per query head: written out if it is the only split, else
+  // published as a partial; the split that finishes last merges
 #pragma unroll
-  for (int w = 1; w < kDecWaves; ++w) m_tot = fmaxf(m_tot, sm_m[w]);
-  float l_tot = 0.f, acc = 0.f;
+  for (int g = 0; g < kG; ++g) {
+    float m_tot = sm_m[0][g];
 #pragma unroll
-  for (int w = 0; w < kDecWaves; ++w) {
-    const float f = __builtin_amdgcn_exp2f(sm_m[w] - m_tot);
-    l_tot += sm_l[w] * f;
-    acc += sm_acc[w][t & (kHeadDim - 1)] * f;
-  }
-  if (a.splits == 1) {
-    if (t < kHeadDim) {
-      store_out(a.out, a.out_is_fp16, bh * kHeadDim + t, acc / l_tot);
-      if (t == 0 && a.lse) a.lse[bh] = (m_tot + __builtin_amdgcn_logf(l_tot)) * kLn2;
+    for (int w = 1; w < kDecWaves; ++w) m_tot = fmaxf(m_tot, sm_m[w][g]);
+    float l_tot = 0.f, acc = 0.f;
+#pragma unroll
+    for (int w = 0; w < kDecWaves; ++w) {
+      const float f = __builtin_amdgcn_exp2f(sm_m[w][g] - m_tot);
+      l_tot += sm_l[w][g] * f;
+      acc += sm_acc[w][g][t & (kHeadDim - 1)] * f;
     }
-    return;
+    if (a.splits == 1) {
+      if (t < kHeadDim) {
+        store_out(a.out, a.out_is_fp16, (bh + g) * kHeadDim + t, acc / l_tot);
+        if (t == 0 && a.lse) a.lse[bh + g] = (m_tot + __builtin_amdgcn_logf(l_tot)) * kLn2;
+      }
+    } else {
+      const size_t ps = (bh + g) * a.splits + split;
+      if (t < kHeadDim) a.part_acc[ps * kHeadDim + t] = acc;
+      if (t == 0) {
+        a.part_ml[ps * 2 + 0] = m_tot;
+        a.part_ml[ps * 2 + 1] = l_tot;
+      }
+    }
   }
-
-  // ---- publish this split's partial; the split that finishes last merges
-  const size_t ps = bh * a.splits + split;
-  if (t < kHeadDim) a.part_acc[ps * kHeadDim + t] = acc;
-  if (t == 0) {
-    a.part_ml[ps * 2 + 0] = m_tot;
-    a.part_ml[ps * 2 + 1] = l_tot;
-  }
+  if (a.splits == 1) return;
   DEC_TRACE(3);
   wait_stores();
   __syncthreads();
@@ -222,35 +246,38 @@ __global__ __launch_bounds__(kDecThreads) void decode_split_kernel(const DecodeA
   // one pass over the splits in chunks of 16, all loads of a chunk in flight at
   // once, with a running maximum (the same rescaling as between pages)
   if (t >= kHeadDim) return;
-  const float* ml = a.part_ml + bh * a.splits * 2;
-  const float* pacc = a.part_acc + bh * a.splits * kHeadDim + t;
-  float mx = kNegBig, l_all = 0.f, o = 0.f;
-  for (int s0 = 0; s0 < a.splits; s0 += 16) {
-    float pm[16], pl[16], pa[16];
+#pragma unroll 1
+  for (int g = 0; g < kG; ++g) {
+    const float* ml = a.part_ml + (bh + g) * a.splits * 2;
+    const float* pacc = a.part_acc + (bh + g) * a.splits * kHeadDim + t;
+    float mx = kNegBig, l_all = 0.f, o = 0.f;
+    for (int s0 = 0; s0 < a.splits; s0 += 16) {
+      float pm[16], pl[16], pa[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int sidx = min(s0 + i, a.splits - 1);
-      pm[i] = team_ld(ml + 2 * sidx);
-      pl[i] = team_ld(ml + 2 * sidx + 1);
-      pa[i] = team_ld(pacc + (size_t)sidx * kHeadDim);
+      for (int i = 0; i < 16; ++i) {
+        const int sidx = min(s0 + i, a.splits - 1);
+        pm[i] = team_ld(ml + 2 * sidx);
+        pl[i] = team_ld(ml + 2 * sidx + 1);
+        pa[i] = team_ld(pacc + (size_t)sidx * kHeadDim);
+      }
+      float cm = mx;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) cm = fmaxf(cm, pm[i]);
+      const float rescale = __builtin_amdgcn_exp2f(mx - cm);
+      l_all *= rescale;
+      o *= rescale;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float f = s0 + i < a.splits ? __builtin_amdgcn_exp2f(pm[i] - cm) : 0.f;
+        l_all += pl[i] * f;
+        o += pa[i] * f;
+      }
+      mx = cm;
     }
-    float cm = mx;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) cm = fmaxf(cm, pm[i]);
-    const float rescale = __builtin_amdgcn_exp2f(mx - cm);
-    l_all *= rescale;
-    o *= rescale;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const float f = s0 + i < a.splits ? __builtin_amdgcn_exp2f(pm[i] - cm) : 0.f;
-      l_all += pl[i] * f;
-      o += pa[i] * f;
-    }
-    mx = cm;
+    store_out(a.out, a.out_is_fp16, (bh + g) * kHeadDim + t, o / l_all);
+    if (t == 0 && a.lse) a.lse[bh + g] = (mx + __builtin_amdgcn_logf(l_all)) * kLn2;
   }
-  store_out(a.out, a.out_is_fp16, bh * kHeadDim + t, o / l_all);
   DEC_TRACE(5);
-  if (t == 0 && a.lse) a.lse[bh] = (mx + __builtin_amdgcn_logf(l_all)) * kLn2;
 }
 
 int env_int(const char* name, int fallback) {
@@ -267,6 +294,17 @@ int env_int(const char* name, int fallback) {
 // merge reads few partial results.  Both knobs can be overridden through the
 // environment for tuning sweeps.
 namespace {
+// Query heads one work-group serves.  Heads of a group share a KV head, so its pages can
+// be loaded once for several of them: that pays on the dense path (4x less traffic; 47 us
+// against 88 us at 32 query / 8 KV heads, 32k tokens).  With a short page list it does not:
+// fewer, heavier work-groups and a merge over more partials (13.9 us against 10.1 us), so
+// there every query head keeps its own work-groups and the later heads of a group find
+// the pages in L2.
+int heads_per_group(const quest_cache& c, int k_pages) {
+  if (k_pages > 0) return 1;
+  const int g = group_size(c);
+  return g % 4 == 0 ? 4 : g % 2 == 0 ? 2 : 1;
+}
 struct SplitPlan {
   int list_len, per_split, splits;
 };
@@ -276,14 +314,21 @@ SplitPlan plan_splits(const quest_cache& c, int k_pages) {
   SplitPlan p;
   p.list_len = k_pages > 0 ? (k_pages < c.max_pages_per_seq ? k_pages : c.max_pages_per_seq)
                            : c.max_pages_per_seq;
-  const long bh = (long)c.batch * c.num_heads;
+  const long bh = (long)c.batch * c.num_heads / heads_per_group(c, k_pages);  // work items per split
   // the knob is in pages of 16 tokens: the same bytes per split for every page size
   const int shift = page_shift_of(c.page_size);
   const long pps = shift >= 0 && ((long)pages_per_split << 4 >> shift) > 0
                        ? ((long)pages_per_split << 4 >> shift)
                        : 1;
   long splits = (p.list_len + pps - 1) / pps;
-  const long cap = max_groups / bh > 0 ? max_groups / bh : 1;
+  // few (sequence, head) items: shorter splits, down to one unit of 16 tokens per wave,
+  // until there is a work-group for every compute unit
+  const long unit = kDecWaves << 4 >> shift > 0 ? (long)(kDecWaves << 4 >> shift) : 1;
+  const long fill = (kComputeUnits + bh - 1) / bh;
+  const long finest = (p.list_len + unit - 1) / unit;
+  if (splits < fill) splits = fill < finest ? fill : finest;
+  const long qh = (long)c.batch * c.num_heads;  // a work-group's weight grows with its heads
+  const long cap = max_groups / qh > 0 ? max_groups / qh : 1;
   if (splits > cap) splits = cap;
   if (splits < 1) splits = 1;
   if (splits > kMaxTeamSize) splits = kMaxTeamSize;
@@ -342,12 +387,21 @@ int launch_sparse_decode(const quest_cache& c, const void* q, const int32_t* top
   a.counters = (uint64_t*)workspace;
   a.part_acc = workspace ? (float*)((char*)workspace + counter_bytes(c)) : nullptr;
   a.part_ml = a.part_acc ? a.part_acc + n_part * kHeadDim : nullptr;
-  const long bh8 = ((long)c.batch * c.num_heads + 7) / 8;
-  const dim3 grid((unsigned)(bh8 * 8 * a.splits));
-  if (c.page_size == 8)
-    hipLaunchKernelGGL(decode_split_kernel<2>, grid, dim3(kDecThreads), 0, s, a);
-  else
-    hipLaunchKernelGGL(decode_split_kernel<4>, grid, dim3(kDecThreads), 0, s, a);
+  const int kg = heads_per_group(c, a.k_pages);
+  const long items8 = ((long)c.batch * c.num_heads / kg + 7) / 8;
+  const dim3 grid((unsigned)(items8 * 8 * a.splits));
+#define QUEST_DECODE_LAUNCH(L, G) \
+  hipLaunchKernelGGL((decode_split_kernel<L, G>), grid, dim3(kDecThreads), 0, s, a)
+  if (c.page_size == 8) {
+    if (kg == 4) QUEST_DECODE_LAUNCH(2, 4);
+    else if (kg == 2) QUEST_DECODE_LAUNCH(2, 2);
+    else QUEST_DECODE_LAUNCH(2, 1);
+  } else {
+    if (kg == 4) QUEST_DECODE_LAUNCH(4, 4);
+    else if (kg == 2) QUEST_DECODE_LAUNCH(4, 2);
+    else QUEST_DECODE_LAUNCH(4, 1);
+  }
+#undef QUEST_DECODE_LAUNCH
   return check_launch("quest_sparse_decode");
 }
 

@@ -101,6 +101,48 @@ __device__ __forceinline__ void fold_page(Softmax& st, PageRegsT<kLoads>& r, con
   st.m = m_new;
 }
 
+// The same unit against kG query heads that share the KV head (grouped-query
+// attention): keys and values are loaded once, the values converted to fp32
+// once, and every head keeps its own online-softmax state.
+template <int kLoads, int kG>
+__device__ __forceinline__ void fold_group(Softmax (&st)[kG], PageRegsT<kLoads>& r,
+                                           const uint4 (&qv)[kG], float scale_log2, int grp) {
+  bool live[kLoads];
+  float vf[kLoads][8];
+#pragma unroll
+  for (int i = 0; i < kLoads; ++i) {
+    live[i] = grp + 4 * i < r.n_valid;  // stale slots of a partial page contribute nothing
+    const uint4 v = live[i] ? r.v[i] : make_uint4(0, 0, 0, 0);
+    vf[i][0] = lo(v.x), vf[i][1] = hi(v.x), vf[i][2] = lo(v.y), vf[i][3] = hi(v.y);
+    vf[i][4] = lo(v.z), vf[i][5] = hi(v.z), vf[i][6] = lo(v.w), vf[i][7] = hi(v.w);
+  }
+#pragma unroll
+  for (int g = 0; g < kG; ++g) {
+    float z[kLoads];
+    float m_new = st[g].m;
+#pragma unroll
+    for (int i = 0; i < kLoads; ++i) {
+      z[i] = live[i] ? row16_sum(dot8(qv[g], r.k[i], 0.f)) * scale_log2 : -INFINITY;
+      m_new = fmaxf(m_new, z[i]);
+    }
+    const float alpha = __builtin_amdgcn_exp2f(st[g].m - m_new);
+    float p[kLoads];
+#pragma unroll
+    for (int i = 0; i < kLoads; ++i) p[i] = __builtin_amdgcn_exp2f(z[i] - m_new);
+    float p_sum = p[0] + p[1];
+    if (kLoads == 4) p_sum += p[kLoads - 2] + p[kLoads - 1];
+    st[g].l = st[g].l * alpha + p_sum;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      float acc = st[g].acc[j] * alpha;
+#pragma unroll
+      for (int i = 0; i < kLoads; ++i) acc += p[i] * vf[i][j];
+      st[g].acc[j] = acc;
+    }
+    st[g].m = m_new;
+  }
+}
+
 // merge the state held by lane ^ mask into this lane's
 __device__ __forceinline__ void merge_lanes(Softmax& st, int mask) {
   const float m_o = __shfl_xor(st.m, mask);

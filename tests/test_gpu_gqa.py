@@ -17,13 +17,14 @@ def ragged(cid, kv_heads, S=16):
                           planted_per_head=4, page_size=S, decode_steps=24)
 
 
-@pytest.mark.parametrize("kv_heads,group", [(3, 2), (2, 4), (1, 8)])
+@pytest.mark.parametrize("kv_heads,group", [(3, 2), (2, 3), (2, 4), (1, 8)])
 def test_chain(kv_heads, group):
     run_chain(ragged(500 + group, kv_heads), steps=5, permute=True, group=group)
 
 
-def test_chain_pages_of_32_tokens():
-    run_chain(ragged(510, 2, S=32), steps=4, permute=True, group=4)
+@pytest.mark.parametrize("S", [8, 32])
+def test_chain_other_page_sizes(S):
+    run_chain(ragged(510 + S, 2, S=S), steps=4, permute=True, group=4)
 
 
 @pytest.mark.parametrize("flags", [0, 1, 8])
