@@ -5,16 +5,18 @@
 //
 // Split-K flash-decoding.  One work-group per (sequence, head, split); each work-group of
 // four waves owns a contiguous slice of the head's page list, its waves take
-// the slice's pages round-robin.  A wave streams one (page, head) block of
-// keys and one of values per step (4 KiB each = 4 wave-wide 16-byte loads
-// each), double-buffered in registers so the next page's eight loads are in
-// flight while the current page is reduced.  Lane l holds channels
-// 8*(l%16)..+7 of tokens l/16 + 4r; q.k is a v_dot2_f32_f16 chain plus a
-// reduction inside the 16-lane DPP row; each DPP row keeps its own online
-// softmax state (running max, denominator, 8 accumulator channels per lane) in
-// fp32, in the log2 domain.  Rows, waves and finally splits are merged with the
-// usual (max, sum, accumulator) rescaling; the split that finishes last merges
-// the partial results of all splits of its head.
+// the slice's pages round-robin.  A wave streams one unit (up to 16 tokens of one
+// page: 4 KiB of keys and 4 KiB of values = 4 + 4 wave-wide 16-byte loads; pages
+// of 32 or 64 tokens are 2 or 4 units, pages of 8 tokens units of 2 + 2 loads) per
+// step, double-buffered in registers so the next unit's loads are in flight while
+// the current one is reduced.  Lane l holds channels 8*(l%16)..+7 of tokens
+// l/16 + 4r; q.k is a v_dot2_f32_f16 chain plus a reduction inside the 16-lane
+// DPP row; each DPP row keeps its own online softmax state (running max,
+// denominator, 8 accumulator channels per lane) in fp32, in the log2 domain.
+// Rows, waves and finally splits are merged with the usual (max, sum,
+// accumulator) rescaling; the split that finishes last merges the partial
+// results of all splits of its head.  With grouped-query attention a work-group
+// of the dense path serves several query heads of one KV head per page load.
 //
 // Single-query attention is a matrix-vector product (about one flop per byte
 // read), far below the machine balance, so there is no MFMA here: the kernel is
