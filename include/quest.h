@@ -75,16 +75,15 @@ typedef enum quest_status {
   QUEST_ERR_HIP = -5          /* the HIP runtime refused the launch          */
 } quest_status;
 
-/* quest_cache.flags.  The first two change no result.
- *  QUEST_FLAG_PERSISTENT_STEP: quest_decode_step runs the whole step as one
- *    launch instead of three whenever the shape allows it (see there).  Its
- *    work-groups wait for each other inside the launch, so it wants the GPU to
- *    itself for those microseconds: if other work keeps part of the grid from
- *    becoming resident, a bounded wait expires and the call reports it through
- *    the status word (never a hang).
+/* quest_cache.flags.
+ *  QUEST_FLAG_SEPARATE_LAUNCHES: quest_decode_step always enqueues the three
+ *    separate launches (estimate, Top-K, attention) instead of letting the
+ *    attention launch select its pages (see there; changes no result except
+ *    the rounding of out / lse).
  *  QUEST_FLAG_DEVICE_FENCES: work-groups that exchange partial results inside a
  *    launch always use device-scope release/acquire fences, as they do on their
- *    own when they find themselves on different dies (for testing that path).
+ *    own when they find themselves on different dies (for testing that path;
+ *    changes no result).
  *  QUEST_FLAG_KEEP_FIRST_PAGE, QUEST_FLAG_KEEP_NEWEST_PAGE: selection policy of
  *    quest_topk and quest_decode_step.  The paper selects purely by score
  *    (Section 3.4) and that is the default; with these flags logical page 0
@@ -93,7 +92,7 @@ typedef enum quest_status {
  *    and among themselves by page index, so they take the first places of the K
  *    and the remaining places are filled by score. */
 enum {
-  QUEST_FLAG_PERSISTENT_STEP = 1,
+  QUEST_FLAG_SEPARATE_LAUNCHES = 1,
   QUEST_FLAG_DEVICE_FENCES = 2,
   QUEST_FLAG_KEEP_FIRST_PAGE = 4,
   QUEST_FLAG_KEEP_NEWEST_PAGE = 8
@@ -167,7 +166,8 @@ int quest_append_estimate(const quest_cache* cache, const void* k_new, const voi
 /* Top-K filtering (Section 3.4): for every (b, h) the K_b = min(k_pages, P_b)
  * pages with the largest score among the P_b = ceil(seq_lens[b]/S) valid ones.
  * Scores compare by value (-0 == +0); of equal scores the lower page index is
- * kept.  QUEST_FLAG_KEEP_* in cache->flags force pages into the list (see there).  topk_idx[b][h][0..K_b) receives the chosen logical page ids in
+ * kept.  QUEST_FLAG_KEEP_* in cache->flags force pages into the list (see
+ * there).  topk_idx[b][h][0..K_b) receives the chosen logical page ids in
  * ascending order, the rest of the row is set to -1.  k_eff (nullable, int32
  * [batch], device) receives K_b.  Deterministic. */
 int quest_topk(const quest_cache* cache, const float* scores, int32_t k_pages,
@@ -196,17 +196,16 @@ int quest_sparse_decode(const quest_cache* cache, const void* q, const int32_t* 
  * accumulated over a different split of the page list (so equal within fp32
  * rounding, not bit for bit).  scores and topk_idx are outputs and also the
  * buffers the phases hand to each other, so they must be provided.
- * workspace: at least n = quest_step_workspace_bytes(cache, k_pages) bytes,
- * zero-filled once after allocation (same rule as for quest_sparse_decode;
- * one buffer of max(both sizes) may serve both calls); calls sharing a
- * workspace must not overlap in time.  The 32-bit word at byte offset n - 256
- * is a sticky status: 0 = every launch so far completed all its work; non-zero
- * = an internal bounded wait of the single launch expired; the outputs of that
- * launch must not be used and the workspace must be zero-filled again.
- * By default the call enqueues the three launches named above (one host call
- * instead of three); with QUEST_FLAG_PERSISTENT_STEP, when page_size == 16,
- * every (sequence, head) can have its team of work-groups resident at once
- * and max_pages_per_seq <= 8192, it is a single launch. */
+ * workspace: at least quest_step_workspace_bytes(cache, k_pages) bytes (the
+ * same size as quest_workspace_bytes gives for k_pages), zero-filled once after
+ * allocation (same rule as for quest_sparse_decode; one buffer may serve both
+ * calls); calls sharing a workspace must not overlap in time.
+ * The call enqueues two launches when k_pages <= 2048 and max_pages_per_seq
+ * <= 8192: the estimate, then an attention launch in which every work-group
+ * first selects the pages of its (sequence, KV head) from the scores, keeps
+ * the list in on-chip memory, and one of them also writes it to topk_idx /
+ * k_eff.  Otherwise, or with QUEST_FLAG_SEPARATE_LAUNCHES, it enqueues the
+ * three launches named above. */
 int quest_step_workspace_bytes(const quest_cache* cache, int32_t k_pages, size_t* out_bytes);
 int quest_decode_step(const quest_cache* cache, const void* k_new, const void* v_new,
                       int32_t k_pool_write, const void* q, int32_t k_pages, float sm_scale,

@@ -14,7 +14,7 @@ _PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG_DIR, "libquest.so")
 
 QUEST_OK = 0
-QUEST_FLAG_PERSISTENT_STEP = 1
+QUEST_FLAG_SEPARATE_LAUNCHES = 1
 QUEST_FLAG_DEVICE_FENCES = 2
 QUEST_FLAG_KEEP_FIRST_PAGE = 4
 QUEST_FLAG_KEEP_NEWEST_PAGE = 8

@@ -207,7 +207,7 @@ int quest_decode_step(const quest_cache* cache, const void* k_new, const void* v
     return QUEST_ERR_SHAPE;
   }
   const size_t need = step_workspace_bytes(*cache, k_pages);
-  if (workspace == nullptr || workspace_bytes < need) {
+  if (need > 0 && (workspace == nullptr || workspace_bytes < need)) {
     set_error("quest_decode_step: workspace of %zu bytes needed, %zu given", need,
               workspace ? workspace_bytes : (size_t)0);
     return QUEST_ERR_WORKSPACE;

@@ -11,7 +11,6 @@
 namespace quest {
 
 constexpr int kHeadDim = 128;   // D: channels per head
-constexpr int kPageSize = 16;   // S: tokens per page the single-launch step is built for
 constexpr int kWave = 64;
 constexpr int kRowBytes = kHeadDim * 2;  // one token's key (or value) of one head
 
@@ -21,12 +20,11 @@ inline int page_shift_of(int page_size) {
   return page_size == 8 ? 3 : page_size == 16 ? 4 : page_size == 32 ? 5 : page_size == 64 ? 6 : -1;
 }
 // One (page, head) block of keys (or of values) is S*D fp16 (4 KiB at S = 16 = 4
-// wave-wide 16-byte loads); one metadata entry (min row + max row) is 512 B.  The metadata
+// wave-wide 16-byte loads); one metadata entry (min row + max row) is kMetaBytes.  The metadata
 // table is head-major, [H][num_phys_pages]: the estimate scans every page of a
 // head, and consecutive physical pages of one head are then contiguous (with
 // page-major entries the same scan touches 512 B every 16 KiB, measured 25 %
 // slower on MI355X).
-constexpr int kBlockBytes = kPageSize * kHeadDim * 2;
 constexpr int kMetaBytes = 2 * kHeadDim * 2;
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
@@ -55,6 +53,11 @@ size_t decode_workspace_bytes(const quest_cache& c, int k_pages);
 int launch_sparse_decode(const quest_cache& c, const void* q, const int32_t* topk_idx, int k_pages,
                          float sm_scale, void* out, int out_is_fp16, float* lse, void* workspace,
                          hipStream_t s);
+
+bool select_decode_supported(const quest_cache& c, int k_pages);
+int launch_select_decode(const quest_cache& c, const void* q, const float* scores, int k_pages,
+                         float sm_scale, int32_t* topk_idx, int32_t* k_eff, void* out,
+                         int out_is_fp16, float* lse, void* workspace, hipStream_t s);
 
 size_t step_workspace_bytes(const quest_cache& c, int k_pages);
 int launch_decode_step(const quest_cache& c, const void* k_new, const void* v_new, int k_pool_write,

@@ -24,6 +24,7 @@
 #include "quest_common.h"
 #include "quest_decode_core.h"
 #include "quest_team.h"
+#include "quest_topk_core.h"
 
 #include <cmath>
 #include <cstdlib>
@@ -35,6 +36,10 @@ namespace {
 constexpr int kComputeUnits = 256;  // MI355X; only used to decide how finely to split
 constexpr int kDecWaves = 4;
 constexpr int kDecThreads = kDecWaves * kWave;
+// With the selection done in the same launch (see decode_split_kernel): 8 waves, the size
+// the selection is fastest at, and room in LDS for a page list of this many entries.
+constexpr int kSelWaves = 8;
+constexpr int kSelListCap = 2048;
 
 #ifdef QUEST_STEP_TRACE
 #define DEC_TRACE(slot)                                                                  \
@@ -53,7 +58,11 @@ struct DecodeArgs {
   const char* q;
   const int32_t* page_table;
   const int32_t* seq_lens;
-  const int32_t* topk_idx;  // nullptr: all pages
+  const int32_t* topk_idx;  // nullptr: all pages (or: selected inside the launch, see scores)
+  const float* scores;      // selection inside the launch: scores [B][kv heads][max_pages] ...
+  int32_t* topk_out;        // ... the list is also written here [B][kv heads][k_pages] ...
+  int32_t* k_eff;           // ... and K_b here (nullable)
+  int policy;               // QUEST_FLAG_KEEP_* bits
   float* part_acc;          // [B*H*splits][D]   un-normalised accumulators
   float* part_ml;           // [B*H*splits][2]   running max (log2 domain), denominator
   void* out;
@@ -84,11 +93,21 @@ struct DecodeArgs {
 // pages.  kG: query heads served by one work-group (they share the KV head, so a page is
 // loaded once for all of them): 1 unless grouped-query attention; a group of G heads is
 // served by G / kG work-groups per split.
-template <int kLoads, int kG>
-__global__ __launch_bounds__(kDecThreads) void decode_split_kernel(const DecodeArgs a) {
+//
+// kSelItems > 0: the page list does not exist yet.  Every work-group first selects the
+// pages of its head itself from the scores (the same selection as quest_topk, kSelItems
+// scores per thread), keeps the list in LDS and uses its own slice; split 0 also writes
+// the list out.  The selection is repeated by every split of a head, which costs nothing
+// that matters (the compute units would idle meanwhile) and saves a launch and the trip
+// of the list through memory.
+template <int kLoads, int kG, int kWaves, int kSelItems>
+__global__ __launch_bounds__(kWaves* kWave) void decode_split_kernel(const DecodeArgs a) {
+  constexpr int kDecWaves = kWaves;
   __shared__ float sm_acc[kDecWaves][kG][kHeadDim];
   __shared__ float sm_m[kDecWaves][kG], sm_l[kDecWaves][kG];
   __shared__ uint32_t sm_before[2];
+  __shared__ TopkShared<kWaves * kWave> sm_topk;
+  __shared__ int32_t sm_list[kSelItems > 0 ? kSelListCap : 1];
 
   const int slot = blockIdx.x & 7;
   const int rank = blockIdx.x >> 3;
@@ -119,6 +138,19 @@ __global__ __launch_bounds__(kDecThreads) void decode_split_kernel(const DecodeA
   const int32_t* idx_row =
       a.topk_idx ? a.topk_idx + ((size_t)b * a.kv_heads + hk) * a.k_pages : nullptr;
   const int32_t* pt = a.page_table + (size_t)b * a.max_pages;
+  if (kSelItems > 0) {
+    const size_t row = (size_t)b * a.kv_heads + hk;
+    const bool writer = split == 0 && h == hk * a.group;  // one work-group per list writes it out
+    int32_t* out_row = a.topk_out + row * a.k_pages;
+    topk_block_put<kWaves * kWave, (kSelItems > 0 ? kSelItems : 1)>(
+        sm_topk, a.scores + row * a.max_pages, a.seq_lens + b, a.max_pages, a.k_pages,
+        [&](int pos, int page) {
+          sm_list[pos] = page;
+          if (writer) out_row[pos] = page;
+        },
+        (writer && hk == 0 && a.k_eff != nullptr) ? a.k_eff + b : nullptr, a.page_shift, a.policy);
+    __syncthreads();
+  }
 
   const int seq_len = a.seq_lens[b];
   uint4 qv[kG];
@@ -142,7 +174,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_split_kernel(const DecodeA
     const int un_v = u & ((1 << a.unit_shift) - 1);
     const int pos = begin + wave + kDecWaves * e;
     int lp_v = -1;
-    if (e < iters && pos < end) lp_v = idx_row ? idx_row[pos] : pos;
+    if (e < iters && pos < end) lp_v = kSelItems > 0 ? sm_list[pos] : idx_row ? idx_row[pos] : pos;
     int ph_v = 0;
     if (lp_v >= 0 && lp_v < a.max_pages) ph_v = pt[lp_v];
     if (lp_v >= num_pages) lp_v = -1;
@@ -352,10 +384,14 @@ size_t decode_workspace_bytes(const quest_cache& c, int k_pages) {
   return counter_bytes(c) + (size_t)c.batch * c.num_heads * splits * (kHeadDim + 2) * sizeof(float);
 }
 
-int launch_sparse_decode(const quest_cache& c, const void* q, const int32_t* topk_idx, int k_pages,
-                         float sm_scale, void* out, int out_is_fp16, float* lse, void* workspace,
-                         hipStream_t s) {
+namespace {
+// scores != nullptr: select inside the launch (topk_out, k_eff receive the list and K_b);
+// the caller has checked select_decode_supported.
+int launch_decode(const quest_cache& c, const void* q, const int32_t* topk_idx, const float* scores,
+                  int32_t* topk_out, int32_t* k_eff, int k_pages, float sm_scale, void* out,
+                  int out_is_fp16, float* lse, void* workspace, hipStream_t s) {
   static const int force_fences = env_int("QUEST_FORCE_DEVICE_FENCES", 0);
+  const bool select = scores != nullptr;
   DecodeArgs a;
   a.k_pool = (const char*)c.k_pool;
   a.v_pool = (const char*)c.v_pool;
@@ -363,12 +399,16 @@ int launch_sparse_decode(const quest_cache& c, const void* q, const int32_t* top
   a.page_table = c.page_table;
   a.seq_lens = c.seq_lens;
   a.topk_idx = topk_idx;
+  a.scores = scores;
+  a.topk_out = topk_out;
+  a.k_eff = k_eff;
+  a.policy = c.flags;
   a.batch = c.batch;
   a.num_heads = c.num_heads;
   a.kv_heads = kv_heads(c);
   a.group = group_size(c);
   a.max_pages = c.max_pages_per_seq;
-  a.k_pages = topk_idx ? k_pages : 0;
+  a.k_pages = (topk_idx || select) ? k_pages : 0;
   const SplitPlan p = plan_splits(c, a.k_pages);
   a.splits = p.splits;
   a.list_len = p.list_len;
@@ -392,8 +432,27 @@ int launch_sparse_decode(const quest_cache& c, const void* q, const int32_t* top
   const int kg = heads_per_group(c, a.k_pages);
   const long items8 = ((long)c.batch * c.num_heads / kg + 7) / 8;
   const dim3 grid((unsigned)(items8 * 8 * a.splits));
+  if (select) {
+    const int mp = c.max_pages_per_seq;
+    const dim3 block(kSelWaves * kWave);
+#define QUEST_SELECT_CASE(I)                                                                 \
+  if (mp <= kSelWaves * kWave * (I)) {                                                       \
+    if (c.page_size == 8)                                                                    \
+      hipLaunchKernelGGL((decode_split_kernel<2, 1, kSelWaves, I>), grid, block, 0, s, a);   \
+    else                                                                                     \
+      hipLaunchKernelGGL((decode_split_kernel<4, 1, kSelWaves, I>), grid, block, 0, s, a);   \
+    return check_launch("quest_decode_step");                                                \
+  }
+    QUEST_SELECT_CASE(2)
+    QUEST_SELECT_CASE(5)
+    QUEST_SELECT_CASE(8)
+    QUEST_SELECT_CASE(16)
+#undef QUEST_SELECT_CASE
+    set_error("quest_decode_step: internal: no selecting kernel for max_pages_per_seq = %d", mp);
+    return QUEST_ERR_SHAPE;
+  }
 #define QUEST_DECODE_LAUNCH(L, G) \
-  hipLaunchKernelGGL((decode_split_kernel<L, G>), grid, dim3(kDecThreads), 0, s, a)
+  hipLaunchKernelGGL((decode_split_kernel<L, G, kDecWaves, 0>), grid, dim3(kDecThreads), 0, s, a)
   if (c.page_size == 8) {
     if (kg == 4) QUEST_DECODE_LAUNCH(2, 4);
     else if (kg == 2) QUEST_DECODE_LAUNCH(2, 2);
@@ -405,6 +464,28 @@ int launch_sparse_decode(const quest_cache& c, const void* q, const int32_t* top
   }
 #undef QUEST_DECODE_LAUNCH
   return check_launch("quest_sparse_decode");
+}
+}  // namespace
+
+int launch_sparse_decode(const quest_cache& c, const void* q, const int32_t* topk_idx, int k_pages,
+                         float sm_scale, void* out, int out_is_fp16, float* lse, void* workspace,
+                         hipStream_t s) {
+  return launch_decode(c, q, topk_idx, nullptr, nullptr, nullptr, k_pages, sm_scale, out, out_is_fp16,
+                       lse, workspace, s);
+}
+
+// Selection and attention in one launch: possible while a row of scores fits the
+// in-register selection of 512 threads and the list fits in LDS.
+bool select_decode_supported(const quest_cache& c, int k_pages) {
+  static const int off = env_int("QUEST_NO_SELECT_DECODE", 0);
+  return !off && !(c.flags & QUEST_FLAG_SEPARATE_LAUNCHES) && c.max_pages_per_seq <= kSelWaves * kWave * 16 && k_pages <= kSelListCap;
+}
+
+int launch_select_decode(const quest_cache& c, const void* q, const float* scores, int k_pages,
+                         float sm_scale, int32_t* topk_idx, int32_t* k_eff, void* out,
+                         int out_is_fp16, float* lse, void* workspace, hipStream_t s) {
+  return launch_decode(c, q, nullptr, scores, topk_idx, k_eff, k_pages, sm_scale, out, out_is_fp16,
+                       lse, workspace, s);
 }
 
 }  // namespace quest

@@ -1,7 +1,6 @@
 // Device-side pieces of the paged decode attention (Figure 5 stage 2 of arXiv
 // 2406.10774): streaming one (page, head) block of keys and values through a
-// wave with an online softmax.  Shared by the stand-alone kernel and the
-// single-launch decode step.  See quest_decode.hip for the scheme.
+// wave with an online softmax.  See quest_decode.hip for the scheme.
 #pragma once
 
 #include "quest_common.h"
@@ -22,7 +21,6 @@ struct PageRegsT {
   uint4 k[kLoads], v[kLoads];
   int n_valid;
 };
-typedef PageRegsT<4> PageRegs;
 
 __device__ __forceinline__ float lo(uint32_t h2) {
   return (float)__builtin_bit_cast(half2_t, h2)[0];
@@ -49,13 +47,6 @@ __device__ __forceinline__ void load_unit(PageRegsT<kLoads>& r, const char* __re
 #pragma unroll
   for (int i = 0; i < kLoads; ++i) r.v[i] = ld16(v_pool + off + i * 1024);
   r.n_valid = min(4 * kLoads, seq_len - (logical_page << page_shift) - unit * (4 * kLoads));
-}
-
-// A whole page of 16 tokens.
-__device__ __forceinline__ void load_page(PageRegs& r, const char* __restrict__ k_pool,
-                                          const char* __restrict__ v_pool, int num_heads, int h,
-                                          int seq_len, int logical_page, int phys, int lane) {
-  load_unit<4>(r, k_pool, v_pool, num_heads, h, seq_len, logical_page, phys, 0, 4, lane);
 }
 
 // n_valid may be anything up to 4 kLoads, also <= 0 (a unit past the end of a

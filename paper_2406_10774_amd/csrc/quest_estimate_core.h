@@ -1,6 +1,5 @@
 // Device-side core of the criticality estimate (attention half of Algorithm 1,
-// Section 3.4 of arXiv 2406.10774), shared by the stand-alone kernel and the
-// single-launch decode step.
+// Section 3.4 of arXiv 2406.10774).
 #pragma once
 
 #include "quest_common.h"

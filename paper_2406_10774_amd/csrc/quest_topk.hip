@@ -34,7 +34,7 @@ __global__ __launch_bounds__(kThreads) void topk_kernel(
   const int h = blockIdx.x;
   const int b = blockIdx.y;
   const size_t bh = (size_t)b * num_heads + h;
-  topk_block<kThreads, kItems, false>(sm, scores + bh * max_pages, seq_lens + b, max_pages, k_pages,
+  topk_block<kThreads, kItems>(sm, scores + bh * max_pages, seq_lens + b, max_pages, k_pages,
                                       topk_idx + bh * k_pages,
                                       (h == 0 && k_eff != nullptr) ? k_eff + b : nullptr, page_shift,
                                       policy);

@@ -1,10 +1,9 @@
 // Device-side core of the Top-K page selection (Section 3.4 of arXiv
-// 2406.10774), shared by the stand-alone kernel and the single-launch decode
-// step.  See quest_topk.hip for the algorithm.
+// 2406.10774), shared by the stand-alone kernel and the attention launch that
+// selects its pages itself.  See quest_topk.hip for the algorithm.
 #pragma once
 
 #include "quest_common.h"
-#include "quest_team.h"
 
 namespace quest {
 
@@ -77,17 +76,6 @@ __device__ __forceinline__ ForcedPages forced_pages(int policy, int num_pages) {
   return f;
 }
 
-#ifdef QUEST_STEP_TRACE
-#define TOPK_TRACE(slot)                                                        \
-  do {                                                                          \
-    if (threadIdx.x == 0 && trace) trace[(slot)] = wall_clock64();              \
-  } while (0)
-#else
-#define TOPK_TRACE(slot) \
-  do {                   \
-  } while (0)
-#endif
-
 template <int kThreads>
 struct TopkShared {
   uint32_t hist[4][256];
@@ -96,16 +84,17 @@ struct TopkShared {
 };
 
 // Selection for one row of scores by one work-group of kThreads threads (all of
-// them must call).  kL2Loads: the scores were written earlier in the same launch
-// by other work-groups of this die, so read them with device-scope loads.
-template <int kThreads, int kItems, bool kL2Loads>
-__device__ __forceinline__ void topk_block(TopkShared<kThreads>& sm, const float* __restrict__ row,
-                                           const int32_t* __restrict__ seq_len_ptr, int max_pages,
-                                           int k_pages, int32_t* __restrict__ out,
-                                           int32_t* __restrict__ k_eff_slot, int page_shift,
-                                           int policy, unsigned long long* trace = nullptr) {
+// them must call).
+// put(position, page) receives the list: positions 0 .. k_pages-1, pages
+// ascending, -1 past the K_b selected ones.
+template <int kThreads, int kItems, class Put>
+__device__ __forceinline__ void topk_block_put(TopkShared<kThreads>& sm,
+                                               const float* __restrict__ row,
+                                               const int32_t* __restrict__ seq_len_ptr,
+                                               int max_pages, int k_pages, Put put,
+                                               int32_t* __restrict__ k_eff_slot, int page_shift,
+                                               int policy) {
   constexpr int kWaves = kThreads / kWave;
-  (void)trace;
   uint32_t(&hist)[4][256] = sm.hist;
   int(&wave_tot)[kWaves] = sm.wave_tot;
   uint32_t& vote = sm.vote;
@@ -122,9 +111,9 @@ __device__ __forceinline__ void topk_block(TopkShared<kThreads>& sm, const float
   for (int j = 0; j < kItems; ++j) {
     // clamped, not predicated: the loads stay independent and all in flight at once
     const int i = min(base + j, max_pages - 1);
-    raw[j] = kL2Loads ? team_ld(row + i) : row[i];
+    raw[j] = row[i];
   }
-  const float raw0 = kL2Loads ? team_ld(row) : row[0];
+  const float raw0 = row[0];
   const int seq_len = *seq_len_ptr;
 
   for (int i = tid; i < 4 * 256; i += kThreads) (&hist[0][0])[i] = 0;
@@ -135,7 +124,7 @@ __device__ __forceinline__ void topk_block(TopkShared<kThreads>& sm, const float
   const int K = min(k_pages, num_pages);
   if (tid == 0 && k_eff_slot != nullptr) *k_eff_slot = K;
   if (K == num_pages) {  // everything is selected: identity list, padded with -1
-    for (int i = tid; i < k_pages; i += kThreads) out[i] = i < K ? i : -1;
+    for (int i = tid; i < k_pages; i += kThreads) put(i, i < K ? i : -1);
     return;
   }
 
@@ -144,13 +133,12 @@ __device__ __forceinline__ void topk_block(TopkShared<kThreads>& sm, const float
   const ForcedPages forced = forced_pages(policy, num_pages);
   if (forced.count >= K) {  // K is 1 or 2 here: the list is the forced pages, lowest first
     if (tid == 0) {
-      out[0] = forced.first ? 0 : num_pages - 1;
-      if (K == 2) out[1] = num_pages - 1;
+      put(0, forced.first ? 0 : num_pages - 1);
+      if (K == 2) put(1, num_pages - 1);
     }
     return;
   }
 
-  TOPK_TRACE(4);
   uint32_t key[kItems];
   bool valid[kItems];
   const uint32_t ref_top = score_key(raw0) & 0xff000000u;
@@ -167,7 +155,6 @@ __device__ __forceinline__ void topk_block(TopkShared<kThreads>& sm, const float
   if (__ballot(differs) != 0 && lane == 0) vote = 1;
   __syncthreads();
   const bool skip_first = __builtin_amdgcn_readfirstlane(vote) == 0;
-  TOPK_TRACE(5);  // uniform: barriers follow
 
   // ---- radix select.  Invariant: the selection is every key whose bits above
   // `shift + 8` ... are greater than `prefix`'s, plus `need` of the keys that
@@ -209,7 +196,6 @@ __device__ __forceinline__ void topk_block(TopkShared<kThreads>& sm, const float
     if (need == hit.count) break;  // the whole bin is selected: no need to split it further
   }
 
-  TOPK_TRACE(6);
   // ---- emit in page order.  key > bin: selected; key in bin: the first `need`.
   const uint32_t T = prefix >> decided_shift;  // decided_shift <= 24
   int n_gt = 0, n_eq = 0;
@@ -233,10 +219,22 @@ __device__ __forceinline__ void topk_block(TopkShared<kThreads>& sm, const float
 #pragma unroll
   for (int j = 0; j < kItems; ++j) {
     const bool sel = gt[j] || (eq[j] && eq_before < need);
-    if (sel) out[gt_before + min(eq_before, need)] = base + j;
+    if (sel) put(gt_before + min(eq_before, need), base + j);
     gt_before += gt[j];
     eq_before += eq[j];
   }
+}
+
+// The list goes to memory.
+template <int kThreads, int kItems>
+__device__ __forceinline__ void topk_block(TopkShared<kThreads>& sm, const float* __restrict__ row,
+                                           const int32_t* __restrict__ seq_len_ptr, int max_pages,
+                                           int k_pages, int32_t* __restrict__ out,
+                                           int32_t* __restrict__ k_eff_slot, int page_shift,
+                                           int policy) {
+  topk_block_put<kThreads, kItems>(
+      sm, row, seq_len_ptr, max_pages, k_pages, [out](int pos, int page) { out[pos] = page; },
+      k_eff_slot, page_shift, policy);
 }
 
 #endif  // __HIPCC__

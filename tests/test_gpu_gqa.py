@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 
 from paper_2406_10774_amd import synth
-from test_gpu_chain import run_chain, run_single_launch_steps
+from test_gpu_chain import run_chain, run_decode_steps
 
 pytestmark = pytest.mark.gpu
 
@@ -29,9 +29,8 @@ def test_chain_other_page_sizes(S):
 
 @pytest.mark.parametrize("flags", [0, 1, 8])
 def test_decode_step(flags):
-    # flags = 1 asks for the single launch, which exists for one KV head per query head
-    # only: the call must fall back to the three launches
-    run_single_launch_steps(ragged(520, 2), steps=8, permute=True, flags=flags, group=4)
+    # two launches, three launches, two launches with the newest page kept
+    run_decode_steps(ragged(520, 2), steps=8, permute=True, flags=flags, group=4)
 
 
 def test_long_context_group_of_4():

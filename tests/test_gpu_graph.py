@@ -1,7 +1,7 @@
 """The library's calls captured in a HIP graph: replays (with eager work and
 synchronisations between them) give the same results as eager calls.  The library
 enqueues kernels only (no memsets, no allocation), so everything is capturable; the
-single-launch step re-arms its own counters, which is what makes a replay valid."""
+attention launch re-arms its own counters, which is what makes a replay valid."""
 import math
 
 import numpy as np
@@ -78,5 +78,5 @@ def test_decode_step_graph_replays_match_eager(flags):
         assert torch.equal(b["idx"], want[1]), replay
         assert (b["out"] - want[2]).abs().max().item() <= 1e-5, replay
         assert torch.equal(layer.meta.view(torch.int16), want[3].view(torch.int16)), replay
-        nbytes = Q.quest_step_workspace_bytes(layer.cache, K)
-        assert int(b["ws"][(nbytes - 256) // 4].item()) == 0
+        n_counters = min(64 * w.batch * w.num_heads, b["ws"].numel())
+        assert int(b["ws"][:n_counters].abs().max().item()) == 0     # counters re-armed

@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 
 from paper_2406_10774_amd import synth
-from test_gpu_chain import run_chain, run_single_launch_steps
+from test_gpu_chain import run_chain, run_decode_steps
 
 pytestmark = pytest.mark.gpu
 
@@ -28,9 +28,8 @@ def test_chain_ragged(S):
 @pytest.mark.parametrize("S", [8, 32, 64])
 @pytest.mark.parametrize("flags", [0, 1])
 def test_decode_step_ragged(S, flags):
-    # flags = 1 asks for the single launch, which exists for 16-token pages only: the call
-    # must fall back to the three launches and give the same results
-    run_single_launch_steps(ragged(S, 300 + S), steps=8, permute=True, flags=flags)
+    # two launches (the attention launch selects its pages) and three launches
+    run_decode_steps(ragged(S, 300 + S), steps=8, permute=True, flags=flags)
 
 
 @pytest.mark.parametrize("S", [8, 32, 64])
