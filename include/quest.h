@@ -201,7 +201,7 @@ int quest_sparse_decode(const quest_cache* cache, const void* q, const int32_t* 
  * allocation (same rule as for quest_sparse_decode; one buffer may serve both
  * calls); calls sharing a workspace must not overlap in time.
  * The call enqueues two launches when k_pages <= 2048 and max_pages_per_seq
- * <= 8192: the estimate, then an attention launch in which every work-group
+ * <= 4096: the estimate, then an attention launch in which every work-group
  * first selects the pages of its (sequence, KV head) from the scores, keeps
  * the list in on-chip memory, and one of them also writes it to topk_idx /
  * k_eff.  Otherwise, or with QUEST_FLAG_SEPARATE_LAUNCHES, it enqueues the

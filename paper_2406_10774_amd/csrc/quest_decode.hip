@@ -150,6 +150,7 @@ __global__ __launch_bounds__(kWaves* kWave) void decode_split_kernel(const Decod
         },
         (writer && hk == 0 && a.k_eff != nullptr) ? a.k_eff + b : nullptr, a.page_shift, a.policy);
     __syncthreads();
+    DEC_TRACE(6);
   }
 
   const int seq_len = a.seq_lens[b];
@@ -446,7 +447,6 @@ int launch_decode(const quest_cache& c, const void* q, const int32_t* topk_idx, 
     QUEST_SELECT_CASE(2)
     QUEST_SELECT_CASE(5)
     QUEST_SELECT_CASE(8)
-    QUEST_SELECT_CASE(16)
 #undef QUEST_SELECT_CASE
     set_error("quest_decode_step: internal: no selecting kernel for max_pages_per_seq = %d", mp);
     return QUEST_ERR_SHAPE;
@@ -474,11 +474,14 @@ int launch_sparse_decode(const quest_cache& c, const void* q, const int32_t* top
                        lse, workspace, s);
 }
 
-// Selection and attention in one launch: possible while a row of scores fits the
-// in-register selection of 512 threads and the list fits in LDS.
+// Selection and attention in one launch: while a row of scores fits the in-register
+// selection of 512 threads with at most 8 keys each and the list fits in LDS.  Every
+// split of a head repeats the selection, so for longer rows (measured at 4097 pages:
+// 34.9 us against 34.2 us) the separate Top-K launch is the faster form.
 bool select_decode_supported(const quest_cache& c, int k_pages) {
   static const int off = env_int("QUEST_NO_SELECT_DECODE", 0);
-  return !off && !(c.flags & QUEST_FLAG_SEPARATE_LAUNCHES) && c.max_pages_per_seq <= kSelWaves * kWave * 16 && k_pages <= kSelListCap;
+  return !off && !(c.flags & QUEST_FLAG_SEPARATE_LAUNCHES) &&
+         c.max_pages_per_seq <= kSelWaves * kWave * 8 && k_pages <= kSelListCap;
 }
 
 int launch_select_decode(const quest_cache& c, const void* q, const float* scores, int k_pages,

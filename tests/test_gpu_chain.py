@@ -174,6 +174,13 @@ def test_decode_step_keeps_forced_pages(flags):
     run_decode_steps(w, steps=12, permute=True, flags=flags)
 
 
+def test_decode_step_long_rows():
+    """Rows of ~3000 pages: the selecting attention launch with 8 keys per thread."""
+    w = synth.Workload(94, "long-rows-step", 2, 2, (16 * 3000 + 5, 16 * 2600), token_budget=16 * 96,
+                       planted_per_head=8, decode_steps=8)
+    run_decode_steps(w, steps=5, permute=True, flags=0)
+
+
 @pytest.mark.parametrize("flags", [0, 1])
 def test_decode_step_config1_full_size(flags):
     run_decode_steps(synth.workload(1), steps=4, permute=False, flags=flags)
