@@ -188,11 +188,13 @@ def topk(scores, seq_lens, page_size, k_pages, keep_first=False, keep_newest=Fal
         for h in range(H):
             s = np.asarray(scores[b, h, :P])
             s = s + 0.0                                      # -0 and +0 rank equal
+            kept = np.zeros(P, bool)                         # above every score, +inf included
             if keep_first:
-                s[0] = np.inf
+                kept[0] = True
             if keep_newest:
-                s[P - 1] = np.inf
-            rank = np.lexsort((np.arange(P), -s))            # last key is primary
+                kept[P - 1] = True
+            s[kept] = np.inf                                 # among themselves: by page index
+            rank = np.lexsort((np.arange(P), -s, ~kept))     # last key is primary
             idx[b, h, :K] = np.sort(rank[:K])
     return idx, k_eff
 

@@ -142,6 +142,9 @@ __global__ __launch_bounds__(kWaves* kWave) void decode_split_kernel(const Decod
     const size_t row = (size_t)b * a.kv_heads + hk;
     const bool writer = split == 0 && h == hk * a.group;  // one work-group per list writes it out
     int32_t* out_row = a.topk_out + row * a.k_pages;
+#ifdef QUEST_STEP_TRACE
+    if (threadIdx.x == 0) sm_topk.trace = a.trace ? a.trace + (size_t)blockIdx.x * 16 : nullptr;
+#endif
     topk_block_put<kWaves * kWave, (kSelItems > 0 ? kSelItems : 1)>(
         sm_topk, a.scores + row * a.max_pages, a.seq_lens + b, a.max_pages, a.k_pages,
         [&](int pos, int page) {

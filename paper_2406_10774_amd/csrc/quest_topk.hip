@@ -2,10 +2,12 @@
 // pages as critical").  One work-group per (sequence, head).
 //
 // Scores are mapped to unsigned 32-bit keys whose integer order equals the
-// order of the float values (-0 folded onto +0).  An MSB-first radix select
-// (8-bit digits, LDS histogram per digit) narrows down the key of the K-th
-// largest score; it stops as soon as every key left in the threshold bin
-// belongs to the selection.  A final pass in page order emits every page above
+// order of the float values (-0 folded onto +0), taken relative to the row's
+// smallest key and shifted left so that the leading bit of the row's range is
+// bit 31.  An MSB-first radix select (8-bit digits, LDS histogram per digit)
+// narrows down the key of the K-th largest score; it stops as soon as every key
+// left in the threshold bin belongs to the selection, or the range's bits are
+// used up.  A final pass in page order emits every page above
 // the threshold bin plus the first `need` pages inside it, each at the position
 // given by a block-wide prefix count, so the output is ascending and the lowest
 // page index wins among equal scores.
@@ -13,11 +15,13 @@
 // The kernel is latency-bound (a few thousand keys per head), so the work is
 // organised to shorten the dependent chain: keys live in registers (thread t
 // owns pages [t*ITEMS, (t+1)*ITEMS)), the score loads are issued before
-// seq_lens is known, a block-wide vote skips the first digit when all keys
-// share their top byte (scores of one head usually share sign and exponent),
-// every wave searches the histogram for the threshold bin itself so a pass
-// needs a single barrier, and same-digit lanes are combined into one LDS atomic
-// in the first pass executed, where nearly all keys hit the same few bins.
+// seq_lens is known, the range normalisation makes the first digit spread the
+// row over the whole histogram (scores of one head share sign and most of the
+// exponent: on raw keys the first one or two digits would decide nothing, and
+// their LDS atomics would all hit the same few bins), every wave searches the
+// histogram for the threshold bin itself so a pass needs a single barrier, and
+// lanes that carry the first lane's digit share one LDS atomic in the first
+// pass (a row with outliers still puts most keys into one bin there).
 #include "quest_common.h"
 #include "quest_topk_core.h"
 
@@ -31,6 +35,9 @@ __global__ __launch_bounds__(kThreads) void topk_kernel(
     int32_t* __restrict__ topk_idx, int32_t* __restrict__ k_eff, int num_heads, int max_pages,
     int k_pages, int page_shift, int policy) {
   __shared__ TopkShared<kThreads> sm;
+#ifdef QUEST_STEP_TRACE
+  if (threadIdx.x == 0) sm.trace = nullptr;
+#endif
   const int h = blockIdx.x;
   const int b = blockIdx.y;
   const size_t bh = (size_t)b * num_heads + h;

@@ -29,6 +29,18 @@ __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
   return v + (row >= 1 ? r0 : 0) + (row >= 2 ? r1 : 0) + (row >= 3 ? r2 : 0);
 }
 
+// Minimum / maximum over the 64 lanes, returned in every lane.
+__device__ __forceinline__ uint32_t wave_min(uint32_t v) {
+#pragma unroll
+  for (int m = 1; m < kWave; m <<= 1) v = min(v, (uint32_t)__shfl_xor((int)v, m));
+  return v;
+}
+__device__ __forceinline__ uint32_t wave_max(uint32_t v) {
+#pragma unroll
+  for (int m = 1; m < kWave; m <<= 1) v = max(v, (uint32_t)__shfl_xor((int)v, m));
+  return v;
+}
+
 // Scan the 256-bin histogram from the top bin down for the bin that holds the
 // need-th largest key.  Lane l owns bins 255-4l .. 252-4l.  Every lane returns
 // the same (bin, keys above the bin, keys in the bin).
@@ -80,8 +92,22 @@ template <int kThreads>
 struct TopkShared {
   uint32_t hist[4][256];
   int wave_tot[kThreads / kWave];
-  uint32_t vote;  // != 0: some key's top byte differs from page 0's
+  uint32_t range[kThreads / kWave][2];  // smallest and largest key seen by each wave
+#ifdef QUEST_STEP_TRACE
+  unsigned long long* trace;  // set by the caller: time stamps of the phases, or nullptr
+#endif
 };
+
+#ifdef QUEST_STEP_TRACE
+#define TOPK_TRACE(slot)                                                           \
+  do {                                                                             \
+    if (threadIdx.x == 0 && sm.trace) sm.trace[(slot)] = wall_clock64();           \
+  } while (0)
+#else
+#define TOPK_TRACE(slot) \
+  do {                   \
+  } while (0)
+#endif
 
 // Selection for one row of scores by one work-group of kThreads threads (all of
 // them must call).
@@ -97,14 +123,14 @@ __device__ __forceinline__ void topk_block_put(TopkShared<kThreads>& sm,
   constexpr int kWaves = kThreads / kWave;
   uint32_t(&hist)[4][256] = sm.hist;
   int(&wave_tot)[kWaves] = sm.wave_tot;
-  uint32_t& vote = sm.vote;
+  uint32_t(&range)[kWaves][2] = sm.range;
   const int tid = threadIdx.x;
   const int lane = lane_id();
   const int wave = tid >> 6;
 
   // issue every load first: this thread's scores (entries past the valid pages
-  // are inside the row, so reading them is safe; they are masked below), the
-  // score of page 0 as the vote's reference, and the sequence length
+  // are inside the row, so reading them is safe; they are masked below) and the
+  // sequence length
   const int base = tid * kItems;
   float raw[kItems];
 #pragma unroll
@@ -113,12 +139,9 @@ __device__ __forceinline__ void topk_block_put(TopkShared<kThreads>& sm,
     const int i = min(base + j, max_pages - 1);
     raw[j] = row[i];
   }
-  const float raw0 = row[0];
   const int seq_len = *seq_len_ptr;
 
   for (int i = tid; i < 4 * 256; i += kThreads) (&hist[0][0])[i] = 0;
-  if (tid == 0) vote = 0;
-  __syncthreads();
 
   const int num_pages = (seq_len + (1 << page_shift) - 1) >> page_shift;
   const int K = min(k_pages, num_pages);
@@ -128,8 +151,9 @@ __device__ __forceinline__ void topk_block_put(TopkShared<kThreads>& sm,
     return;
   }
 
-  // Pages that are kept whatever their score rank above every score (key ~0;
-  // finite scores map below 0xff800000) and, like equal scores, by page index.
+  // Pages that are kept whatever their score rank above every score and, like
+  // equal scores, by page index: they stay out of the histograms, take their
+  // places off the count, and are emitted with the keys above the threshold.
   const ForcedPages forced = forced_pages(policy, num_pages);
   if (forced.count >= K) {  // K is 1 or 2 here: the list is the forced pages, lowest first
     if (tid == 0) {
@@ -139,35 +163,43 @@ __device__ __forceinline__ void topk_block_put(TopkShared<kThreads>& sm,
     return;
   }
 
+  // Keys of the valid, not forced pages; their range over the row.
   uint32_t key[kItems];
-  bool valid[kItems];
-  const uint32_t ref_top = score_key(raw0) & 0xff000000u;
-  bool differs = false;
+  bool valid[kItems], kept[kItems];
+  uint32_t lo = 0xffffffffu, hi = 0u;
 #pragma unroll
   for (int j = 0; j < kItems; ++j) {
     key[j] = score_key(raw[j]);
-    valid[j] = base + j < num_pages;
-    if (forced.is(base + j))
-      key[j] = 0xffffffffu;
-    else
-      differs |= valid[j] && (key[j] & 0xff000000u) != ref_top;
+    kept[j] = forced.is(base + j);
+    valid[j] = base + j < num_pages && !kept[j];
+    if (valid[j]) lo = min(lo, key[j]), hi = max(hi, key[j]);
   }
-  if (__ballot(differs) != 0 && lane == 0) vote = 1;
+  lo = wave_min(lo);
+  hi = wave_max(hi);
+  if (lane == 0) range[wave][0] = lo, range[wave][1] = hi;
+  TOPK_TRACE(7);  // scores there
   __syncthreads();
-  const bool skip_first = __builtin_amdgcn_readfirstlane(vote) == 0;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) lo = min(lo, range[w][0]), hi = max(hi, range[w][1]);
+  lo = __builtin_amdgcn_readfirstlane(lo);
+  hi = __builtin_amdgcn_readfirstlane(hi);
 
-  // ---- radix select.  Invariant: the selection is every key whose bits above
-  // `shift + 8` ... are greater than `prefix`'s, plus `need` of the keys that
-  // match `prefix` on the bits decided so far.
-  uint32_t prefix = skip_first ? ref_top : 0u;
-  // with the first digit skipped the forced keys (top byte 0xff) are never counted:
-  // they are above the threshold for certain
-  int need = skip_first ? K - forced.count : K;
-  int decided_shift = skip_first ? 24 : 32;  // bits [decided_shift, 32) of the threshold are known
-  bool first_pass = true;
+  // ---- radix select on (key - lo), shifted left so that the range's leading bit is
+  // bit 31: the first digit already spreads the row over the histogram, and only
+  // ceil(bits / 8) digits exist.  Monotone and one-to-one on the row's keys, so order
+  // and ties are those of the scores.  Invariant: the selection is every key greater
+  // than `prefix` on the bits decided so far, plus `need` of the keys that match it.
+  const int bits = hi > lo ? 32 - __builtin_clz(hi - lo) : 0;
+  const int align = 32 - bits;  // 32 when all keys are equal: nothing to decide
+#pragma unroll
+  for (int j = 0; j < kItems; ++j) key[j] = bits ? (key[j] - lo) << align : 0u;
+  const int n_pass = (bits + 7) >> 3;
+  uint32_t prefix = 0u;
+  int need = K - forced.count;  // the forced pages are in the list for certain
+  int decided_shift = 32;       // bits [decided_shift, 32) of the threshold are known
 #pragma unroll
   for (int pass = 0; pass < 4; ++pass) {
-    if (pass == 0 && skip_first) continue;
+    if (pass >= n_pass) break;
     const int shift = 24 - 8 * pass;
     const uint32_t high_mask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
     uint32_t* hp = hist[pass];
@@ -175,8 +207,9 @@ __device__ __forceinline__ void topk_block_put(TopkShared<kThreads>& sm,
     for (int j = 0; j < kItems; ++j) {
       const bool act = valid[j] && (key[j] & high_mask) == prefix;
       const uint32_t digit = (key[j] >> shift) & 255u;
-      if (first_pass) {
-        // most lanes carry the same digit here: one atomic for all of them
+      if (pass == 0) {
+        // a row with outliers puts nearly all keys into one bin here: lanes that
+        // carry the first active lane's digit share one atomic
         const uint32_t dd = act ? digit : 0xffffffffu;
         const uint32_t d0 = __builtin_amdgcn_readfirstlane(dd);
         const unsigned long long same = __ballot(dd == d0);
@@ -187,23 +220,23 @@ __device__ __forceinline__ void topk_block_put(TopkShared<kThreads>& sm,
         atomicAdd(&hp[digit], 1u);
       }
     }
-    first_pass = false;
     __syncthreads();
     const BinHit hit = find_bin(hp, need, lane);
     prefix |= (uint32_t)hit.bin << shift;
     need -= hit.above;
     decided_shift = shift;
+    TOPK_TRACE(8 + pass);
     if (need == hit.count) break;  // the whole bin is selected: no need to split it further
   }
 
   // ---- emit in page order.  key > bin: selected; key in bin: the first `need`.
-  const uint32_t T = prefix >> decided_shift;  // decided_shift <= 24
+  const uint32_t T = decided_shift < 32 ? prefix >> decided_shift : 0u;
   int n_gt = 0, n_eq = 0;
   bool gt[kItems], eq[kItems];
 #pragma unroll
   for (int j = 0; j < kItems; ++j) {
-    const uint32_t kd = key[j] >> decided_shift;
-    gt[j] = valid[j] && kd > T;
+    const uint32_t kd = decided_shift < 32 ? key[j] >> decided_shift : 0u;
+    gt[j] = (valid[j] && kd > T) || kept[j];
     eq[j] = valid[j] && kd == T;
     n_gt += gt[j];
     n_eq += eq[j];

@@ -170,6 +170,49 @@ def test_topk_long_rows(max_pages, lens):
         assert np.array_equal(idx.cpu().numpy(), want), (max_pages, k_pages)
 
 
+@pytest.mark.parametrize("max_pages", [700, 3000, 6000])
+def test_topk_key_ranges(max_pages):
+    """Rows whose keys span very different ranges (the selection works on keys relative to
+    the row's smallest one, aligned to the range's leading bit): a few ulps, one outlier at
+    either end, the whole float range, infinities among the valid scores."""
+    import torch
+    from paper_2406_10774_amd import binding as Q
+    B, H, S = 1, 8, 16
+    dev = "cuda:0"
+    rng = np.random.default_rng(max_pages)
+    P = max_pages - 3
+    sc = (rng.standard_normal((B, H, max_pages)) * 30 + 200).astype(np.float32)
+    base = np.float32(137.5).view(np.uint32)
+    sc[0, 0] = (base + rng.integers(0, 2, max_pages).astype(np.uint32)).view(np.float32)    # 1 bit
+    sc[0, 1] = (base + rng.integers(0, 300, max_pages).astype(np.uint32)).view(np.float32)  # 9 bits
+    sc[0, 2, 5] = 3e38                                 # one outlier above
+    sc[0, 3, 7] = -3e38                                # one outlier below
+    sc[0, 4] = (rng.standard_normal(max_pages) * 1e30).astype(np.float32)
+    sc[0, 4, ::7] = rng.standard_normal(len(sc[0, 4, ::7])).astype(np.float32) * 1e-30   # all 32 bits
+    sc[0, 5, 3] = np.inf
+    sc[0, 5, 11] = -np.inf
+    sc[0, 5, 12] = np.inf
+    sc[0, 6] = 1e-42                                   # subnormals ...
+    sc[0, 6, ::2] = -1e-42                             # ... of both signs
+    sc[0, 7, :P // 2] = 5.0                            # two values only
+    sc[0, 7, P // 2:] = 6.0
+    lens = np.array([16 * P - 2], np.int32)
+    dummy = torch.zeros((1, H, S, 128), dtype=torch.float16, device=dev)
+    meta = torch.zeros((H, 1, 2, 128), dtype=torch.float16, device=dev)
+    pt = torch.zeros((B, max_pages), dtype=torch.int32, device=dev)
+    scd = torch.from_numpy(sc).to(dev)
+    for policy in (0, 12):
+        cache = Q.Cache(dummy, dummy, meta, pt, torch.from_numpy(lens).to(dev), flags=policy)
+        for k_pages in (1, 2, 3, 17, 128, P // 2, P // 2 + 1, P - 1):
+            idx = torch.full((B, H, k_pages), -7, dtype=torch.int32, device=dev)
+            Q.quest_topk(cache, scd, k_pages, idx, None)
+            want, _ = O.topk(sc, lens, S, k_pages, keep_first=bool(policy & 4),
+                             keep_newest=bool(policy & 8))
+            got = idx.cpu().numpy()
+            for h in range(H):
+                assert np.array_equal(got[0, h], want[0, h]), (max_pages, policy, k_pages, h)
+
+
 @pytest.mark.parametrize("policy", [4, 8, 12])
 @pytest.mark.parametrize("max_pages,lens", [
     (210, (1, 16 * 3 + 7, 16 * 203 + 5, 16 * 2)),      # one page, a few, many, two
