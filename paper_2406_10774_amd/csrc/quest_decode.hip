@@ -52,6 +52,14 @@ constexpr int kSelListCap = 2048;
   } while (0)
 #endif
 
+// The same value in a register that no load is outstanding for: the compiler waits for
+// `v` here, once, instead of before every later use it cannot order against other loads.
+__device__ __forceinline__ int settled(int v) {
+  int r;
+  asm volatile("v_mov_b32 %0, %1" : "=v"(r) : "v"(v));
+  return r;
+}
+
 struct DecodeArgs {
   const char* k_pool;
   const char* v_pool;
@@ -182,7 +190,6 @@ __global__ __launch_bounds__(kWaves* kWave) void decode_split_kernel(const Decod
     int ph_v = 0;
     if (lp_v >= 0 && lp_v < a.max_pages) ph_v = pt[lp_v];
     if (lp_v >= num_pages) lp_v = -1;
-    const int n_here = min(kWave, units - chunk);
     if (__builtin_amdgcn_readlane(ph_v, 0) >= 0) DEC_TRACE(1);
 
 #define QUEST_LOAD_UNIT(regs, i)                                                               \
@@ -196,21 +203,34 @@ __global__ __launch_bounds__(kWaves* kWave) void decode_split_kernel(const Decod
     else                                                  \
       fold_group(st, regs, qv, a.scale_log2, grp);        \
   } while (0)
+    // The valid units of a round are its first n lanes (lists are ascending and padded
+    // at the end).  Two units in flight per wave: the next one is requested before the
+    // current one is folded.  Every load inside the loop is unconditional and the index
+    // registers are detached from the loads that produced them (one wait here), so the
+    // compiler's wait counts inside the loop are exact: a conditional load, or an index
+    // still marked as in flight, makes it wait for everything outstanding at every
+    // step, which leaves a single unit in flight.
+    const unsigned long long live = __ballot(lp_v >= 0);
+    const int n = live == ~0ull ? kWave : __ffsll((long long)~live) - 1;
+    lp_v = settled(lp_v);
+    ph_v = settled(ph_v);
     PageRegsT<kLoads> ra, rb;
-    int j = 0;
-    int lp = __builtin_amdgcn_readlane(lp_v, 0);
-    if (lp >= 0) QUEST_LOAD_UNIT(ra, 0);
-    while (lp >= 0) {
-      int lp_b = -1;
-      if (j + 1 < n_here) lp_b = __builtin_amdgcn_readlane(lp_v, j + 1);
-      if (lp_b >= 0) QUEST_LOAD_UNIT(rb, j + 1);
-      QUEST_FOLD(ra);
-      if (lp_b < 0) break;
-      j += 2;
-      lp = -1;
-      if (j < n_here) lp = __builtin_amdgcn_readlane(lp_v, j);
-      if (lp >= 0) QUEST_LOAD_UNIT(ra, j);
-      QUEST_FOLD(rb);
+    if (n > 0) {
+      QUEST_LOAD_UNIT(ra, 0);
+      int j = 0;
+      for (; j + 2 < n; j += 2) {
+        QUEST_LOAD_UNIT(rb, j + 1);
+        QUEST_FOLD(ra);
+        QUEST_LOAD_UNIT(ra, j + 2);
+        QUEST_FOLD(rb);
+      }
+      if (j + 1 < n) {
+        QUEST_LOAD_UNIT(rb, j + 1);
+        QUEST_FOLD(ra);
+        QUEST_FOLD(rb);
+      } else {
+        QUEST_FOLD(ra);
+      }
     }
 #undef QUEST_LOAD_UNIT
 #undef QUEST_FOLD

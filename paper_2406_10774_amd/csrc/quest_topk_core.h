@@ -29,17 +29,18 @@ __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
   return v + (row >= 1 ? r0 : 0) + (row >= 2 ? r1 : 0) + (row >= 3 ? r2 : 0);
 }
 
-// Minimum / maximum over the 64 lanes, returned in every lane.
+// Minimum / maximum over the 64 lanes, returned in every lane (wave-uniform): DPP
+// row shifts gather each 16-lane row's result in its last lane (a lane without a
+// source keeps its own value), the four rows are combined on the scalar side.
 __device__ __forceinline__ uint32_t wave_min(uint32_t v) {
-#pragma unroll
-  for (int m = 1; m < kWave; m <<= 1) v = min(v, (uint32_t)__shfl_xor((int)v, m));
-  return v;
+  v = min(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x111, 0xf, 0xf, false));
+  v = min(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x112, 0xf, 0xf, false));
+  v = min(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x114, 0xf, 0xf, false));
+  v = min(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x118, 0xf, 0xf, false));
+  return min(min((uint32_t)__builtin_amdgcn_readlane((int)v, 15), (uint32_t)__builtin_amdgcn_readlane((int)v, 31)),
+             min((uint32_t)__builtin_amdgcn_readlane((int)v, 47), (uint32_t)__builtin_amdgcn_readlane((int)v, 63)));
 }
-__device__ __forceinline__ uint32_t wave_max(uint32_t v) {
-#pragma unroll
-  for (int m = 1; m < kWave; m <<= 1) v = max(v, (uint32_t)__shfl_xor((int)v, m));
-  return v;
-}
+__device__ __forceinline__ uint32_t wave_max(uint32_t v) { return ~wave_min(~v); }
 
 // Scan the 256-bin histogram from the top bin down for the bin that holds the
 // need-th largest key.  Lane l owns bins 255-4l .. 252-4l.  Every lane returns
@@ -183,6 +184,7 @@ __device__ __forceinline__ void topk_block_put(TopkShared<kThreads>& sm,
   for (int w = 0; w < kWaves; ++w) lo = min(lo, range[w][0]), hi = max(hi, range[w][1]);
   lo = __builtin_amdgcn_readfirstlane(lo);
   hi = __builtin_amdgcn_readfirstlane(hi);
+  TOPK_TRACE(12);
 
   // ---- radix select on (key - lo), shifted left so that the range's leading bit is
   // bit 31: the first digit already spreads the row over the histogram, and only
@@ -208,19 +210,21 @@ __device__ __forceinline__ void topk_block_put(TopkShared<kThreads>& sm,
       const bool act = valid[j] && (key[j] & high_mask) == prefix;
       const uint32_t digit = (key[j] >> shift) & 255u;
       if (pass == 0) {
-        // a row with outliers puts nearly all keys into one bin here: lanes that
-        // carry the first active lane's digit share one atomic
+        // a row with outliers puts nearly all keys into one bin here: the lanes that
+        // carry lane 0's digit are counted by lane 0 alone (one atomic per lane at most,
+        // all lanes are active)
         const uint32_t dd = act ? digit : 0xffffffffu;
         const uint32_t d0 = __builtin_amdgcn_readfirstlane(dd);
-        const unsigned long long same = __ballot(dd == d0);
-        if (d0 != 0xffffffffu && lane == __ffsll((long long)same) - 1)
-          atomicAdd(&hp[d0], (uint32_t)__popcll(same));
-        if (act && dd != d0) atomicAdd(&hp[digit], 1u);
+        const uint32_t n_same = (uint32_t)__popcll(__ballot(dd == d0));
+        const bool go = lane == 0 ? act : (act && dd != d0);
+        if (go) atomicAdd(&hp[digit], lane == 0 ? n_same : 1u);
       } else if (act) {
         atomicAdd(&hp[digit], 1u);
       }
     }
+    if (pass == 0) TOPK_TRACE(13);
     __syncthreads();
+    if (pass == 0) TOPK_TRACE(14);
     const BinHit hit = find_bin(hp, need, lane);
     prefix |= (uint32_t)hit.bin << shift;
     need -= hit.above;
