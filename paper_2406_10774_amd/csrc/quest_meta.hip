@@ -38,17 +38,19 @@ __global__ __launch_bounds__(kBuildWaves* kWave) void build_meta_kernel(
   const int page0 = (blockIdx.x * kBuildWaves + wave) * kPagesPerWave;
   if (page0 >= num_pages) return;
 
+  // All page-table entries, then all key loads, none under a condition (a load inside
+  // a branch is waited for before the branch ends, which would serialise the pages): a
+  // page past the end re-reads the wave's first page and is skipped below.
   uint4 buf[kPagesPerWave][kLoads];
   int phys[kPagesPerWave];
 #pragma unroll
-  for (int u = 0; u < kPagesPerWave; ++u) {
-    const int p = page0 + u;
-    if (p < num_pages) {
-      phys[u] = page_table[(size_t)b * max_pages + p];
-      const char* blk = k_pool + ((size_t)phys[u] * num_heads + h) * (kS * kRowBytes);
+  for (int u = 0; u < kPagesPerWave; ++u)
+    phys[u] = page_table[(size_t)b * max_pages + (page0 + u < num_pages ? page0 + u : page0)];
 #pragma unroll
-      for (int r = 0; r < kLoads; ++r) buf[u][r] = ld16(blk + r * 1024 + lane * 16);
-    }
+  for (int u = 0; u < kPagesPerWave; ++u) {
+    const char* blk = k_pool + ((size_t)phys[u] * num_heads + h) * (kS * kRowBytes);
+#pragma unroll
+    for (int r = 0; r < kLoads; ++r) buf[u][r] = ld16(blk + r * 1024 + lane * 16);
   }
 #pragma unroll
   for (int u = 0; u < kPagesPerWave; ++u) {
