@@ -48,6 +48,9 @@ def parse():
     ap.add_argument("--kv-heads", type=int, default=0,
                     help="grouped-query attention: KV heads (a divisor of the workload's heads); "
                          "the workload's heads stay the query heads.  Implies --no-cpu-baseline")
+    ap.add_argument("--batch", type=int, default=0,
+                    help="that many copies of the workload's (single) sequence in one batch: the "
+                         "throughput regime.  Implies --no-cpu-baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="also time eager (per-call) launches")
     return ap.parse_args()
@@ -69,6 +72,12 @@ def main():
     n_layers = args.layers
     visits = -(-n_total // n_layers)                      # appends per layer buffer
     over = {"page_size": args.page_size} if args.page_size else {}
+    if args.batch:
+        base = synth.workload(args.config)
+        assert base.batch == 1, "--batch replicates a single-sequence workload"
+        over["batch"] = args.batch
+        over["seq_lens"] = tuple(base.seq_lens) * args.batch
+        args.no_cpu_baseline = True
     wq = synth.workload(args.config, decode_steps=visits + 1, **over)   # query side
     Hq = wq.num_heads
     if args.kv_heads:
@@ -259,7 +268,9 @@ def main():
     achieved = dom_bytes / dom_us / 1e3
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                "traffic": load_traffic(dom)}
+                # the counters were collected on the headline configuration only
+                "traffic": load_traffic(dom) if args.config == 1 and not (
+                    args.batch or args.page_size or args.kv_heads) else None}
 
     # ---------------------------------------------------------- CPU baseline
     cpu = None
