@@ -289,6 +289,10 @@ def test_topk_special_cases():
     sc2 = np.array([[[1.0, 5.0, 5.0, 5.0, 0.0, 5.0, 7.0, -1.0, 5.0, 2.0]]])
     idx, _ = O.topk(sc2, lens, S, 3)
     assert list(idx[0, 0]) == [1, 2, 6]                          # 7, then the two lowest 5s
+    sc3 = np.array([[[-0.0, 0.0, -0.0, 0.0, -1.0, -2.0, -0.0, 0.0, -3.0, -4.0]]])
+    idx, _ = O.topk(sc3, lens, S, 2)
+    assert list(idx[0, 0]) == [0, 1]                             # -0 and +0 are one score
+    assert list(idx[0, 0]) == brute_topk(sc3[0, 0], 2)
 
 
 @pytest.mark.parametrize("keep_first,keep_newest", [(True, False), (False, True), (True, True)])
