@@ -277,6 +277,47 @@ def test_sparse_decode_against_oracle(ragged):
     assert (np.abs(got16.astype(np.float64) - w16.astype(np.float64)) <= ulp).all()
 
 
+def test_agreement_tells_a_single_wrong_page(ragged):
+    """How sharp the comparison is: the stated bar for attention is 2e-3, the observed
+    distance to the oracle is fp32 rounding noise.  A list that is wrong in its least
+    important page (dropped, or replaced by the best page that was not selected) moves the
+    oracle's own answer by far more than that noise, so such a mistake in the kernel or in
+    the gather could not hide behind it.  The mistakes are planted in the oracle's input."""
+    w, table, N, k_pool, v_pool, q, lens, layer = ragged
+    S = w.page_size
+    meta = O.build_meta(k_pool, table, lens)
+    sc = O.estimate(meta, q, table, lens, S)
+    scale = 1 / math.sqrt(w.head_dim)
+    k_pages = 24
+    idx, keff = O.topk(sc, lens, S, k_pages)
+    want, _ = O.sparse_decode(k_pool, v_pool, q, table, lens, idx, scale)
+    got, _ = layer.decode(q, idx, k_pages)
+    noise = np.abs(got - want).max()
+    assert noise <= 2e-5                                # regression guard, far inside the stated bar
+    from oracle.diagnostics import attention_weights
+    for b in range(w.batch):
+        P = O.num_pages(lens[b], S)
+        if keff[b] < 2 or keff[b] == P:
+            continue                                    # nothing to drop, or nothing left to swap in
+        for h in range(w.num_heads):
+            wts = attention_weights(k_pool, q[b, h], table[b], lens[b], h, scale)
+            mass = np.zeros(P)
+            np.add.at(mass, np.arange(int(lens[b])) // S, wts)
+            chosen = idx[b, h, :keff[b]]
+            least = chosen[np.argmin(mass[chosen])]
+            others = np.setdiff1d(np.arange(P), chosen)
+            swap_in = others[np.argmax(mass[others])]
+            for wrong in (np.where(chosen == least, -1, chosen),                 # dropped (kept sorted: -1 moved last)
+                          np.sort(np.where(chosen == least, swap_in, chosen))):  # replaced
+                row = np.full(k_pages, -1, np.int32)
+                ok = wrong[wrong >= 0]
+                row[:len(ok)] = np.sort(ok)
+                bad = idx.copy()
+                bad[b, h] = row
+                moved, _ = O.sparse_decode(k_pool, v_pool, q, table, lens, bad, scale)
+                assert np.abs(moved[b, h] - want[b, h]).max() > 10 * noise, (b, h)
+
+
 def test_dense_path_is_dense_attention(ragged):
     w, table, N, k_pool, v_pool, q, lens, layer = ragged
     scale = 0.07
