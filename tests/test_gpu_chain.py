@@ -181,6 +181,15 @@ def test_decode_step_long_rows():
     run_decode_steps(w, steps=5, permute=True, flags=0)
 
 
+@pytest.mark.parametrize("k_pages", [2048, 2049])
+def test_decode_step_at_the_limits_of_the_selecting_launch(k_pages):
+    """Rows of 4096 pages and a list of 2048 pages are the largest the attention launch
+    selects for itself; one page more in the list and the call is three launches."""
+    w = synth.Workload(96, "limits-step", 1, 2, (16 * 4095 + 9,), token_budget=16 * k_pages,
+                       planted_per_head=8, decode_steps=4)
+    run_decode_steps(w, steps=3, permute=True, flags=0)
+
+
 @pytest.mark.parametrize("flags", [0, 1])
 def test_decode_step_config1_full_size(flags):
     run_decode_steps(synth.workload(1), steps=4, permute=False, flags=flags)
