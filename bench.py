@@ -48,6 +48,8 @@ def parse():
     ap.add_argument("--kv-heads", type=int, default=0,
                     help="grouped-query attention: KV heads (a divisor of the workload's heads); "
                          "the workload's heads stay the query heads.  Implies --no-cpu-baseline")
+    ap.add_argument("--token-budget", type=int, default=0,
+                    help="token budget instead of the workload's own (K = budget / page size)")
     ap.add_argument("--batch", type=int, default=0,
                     help="that many copies of the workload's (single) sequence in one batch: the "
                          "throughput regime.  Implies --no-cpu-baseline")
@@ -72,6 +74,8 @@ def main():
     n_layers = args.layers
     visits = -(-n_total // n_layers)                      # appends per layer buffer
     over = {"page_size": args.page_size} if args.page_size else {}
+    if args.token_budget:
+        over["token_budget"] = args.token_budget
     if args.batch:
         base = synth.workload(args.config)
         assert base.batch == 1, "--batch replicates a single-sequence workload"
@@ -275,7 +279,7 @@ def main():
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                 # the counters were collected on the headline configuration only
                 "traffic": load_traffic(dom) if args.config == 1 and not (
-                    args.batch or args.page_size or args.kv_heads) else None}
+                    args.batch or args.page_size or args.kv_heads or args.token_budget) else None}
 
     # ---------------------------------------------------------- CPU baseline
     cpu = None
