@@ -253,9 +253,10 @@ def main():
     k_app = kernel_us(lambda i: Q.quest_append_meta(caches[i], kn_all[i], vn_all[i], True))
     k_dense = kernel_us(lambda i: Q.quest_sparse_decode(caches[i], q_all[i], None, 0, scale, out,
                                                         None, ws), reps=1)
-    # the attention launch that selects its own pages has no entry point of its own: its
-    # duration is the two-launch step minus the estimate launch, both timed the same way
-    k_seldec = kernel_us(two_launch_step) - k_appest if selects_inside else float("nan")
+    # the attention launch that selects its own pages (the second launch of the one-call step)
+    k_seldec = kernel_us(lambda i: Q.quest_select_decode(caches[i], q_all[i], scores, K, scale, idx,
+                                                         out, workspace=ws_step)) \
+        if selects_inside else float("nan")
     score_bytes = float(np.mean([H * p * 4 for p in pages_steps]))
     kernels = {
         "append_meta_us": round(k_app, 3),

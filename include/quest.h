@@ -188,6 +188,20 @@ int quest_sparse_decode(const quest_cache* cache, const void* q, const int32_t* 
                         int32_t k_pages, float sm_scale, void* out, int32_t out_is_fp16,
                         float* lse, void* workspace, size_t workspace_bytes, void* stream);
 
+/* quest_topk followed by quest_sparse_decode with the list just selected
+ * (Section 3.4 and Figure 5, stage 2), for scores that already exist.  topk_idx
+ * / k_eff receive exactly what quest_topk would write, bit for bit; out and lse
+ * are the attention result of quest_sparse_decode over that list (equal within
+ * fp32 rounding: the list is split differently).  One launch, in which every
+ * work-group first selects the pages of its (sequence, KV head) from the scores
+ * and keeps the list in on-chip memory, when k_pages <= 2048 and
+ * max_pages_per_seq <= 4096 and QUEST_FLAG_SEPARATE_LAUNCHES is not set; else
+ * the two launches.  workspace: as for quest_sparse_decode with this k_pages. */
+int quest_select_decode(const quest_cache* cache, const void* q, const float* scores,
+                        int32_t k_pages, float sm_scale, int32_t* topk_idx, int32_t* k_eff,
+                        void* out, int32_t out_is_fp16, float* lse, void* workspace,
+                        size_t workspace_bytes, void* stream);
+
 /* The whole decode step of one layer in one call (Algorithm 1 and
  * Figure 5): quest_append_estimate (quest_estimate if k_new == NULL), then
  * quest_topk, then quest_sparse_decode with the list just selected.  k_pool /
@@ -200,12 +214,9 @@ int quest_sparse_decode(const quest_cache* cache, const void* q, const int32_t* 
  * same size as quest_workspace_bytes gives for k_pages), zero-filled once after
  * allocation (same rule as for quest_sparse_decode; one buffer may serve both
  * calls); calls sharing a workspace must not overlap in time.
- * The call enqueues two launches when k_pages <= 2048 and max_pages_per_seq
- * <= 4096: the estimate, then an attention launch in which every work-group
- * first selects the pages of its (sequence, KV head) from the scores, keeps
- * the list in on-chip memory, and one of them also writes it to topk_idx /
- * k_eff.  Otherwise, or with QUEST_FLAG_SEPARATE_LAUNCHES, it enqueues the
- * three launches named above. */
+ * The call enqueues the estimate, then what quest_select_decode enqueues: two
+ * launches when k_pages <= 2048 and max_pages_per_seq <= 4096 and
+ * QUEST_FLAG_SEPARATE_LAUNCHES is not set, else three. */
 int quest_step_workspace_bytes(const quest_cache* cache, int32_t k_pages, size_t* out_bytes);
 int quest_decode_step(const quest_cache* cache, const void* k_new, const void* v_new,
                       int32_t k_pool_write, const void* q, int32_t k_pages, float sm_scale,

@@ -22,7 +22,7 @@ STATUS_NAMES = {0: "QUEST_OK", -1: "QUEST_ERR_NULL", -2: "QUEST_ERR_SHAPE",
                 -3: "QUEST_ERR_UNSUPPORTED", -4: "QUEST_ERR_WORKSPACE", -5: "QUEST_ERR_HIP"}
 
 EXPORTS = ("quest_workspace_bytes", "quest_build_meta", "quest_append_meta", "quest_estimate",
-           "quest_append_estimate", "quest_topk", "quest_sparse_decode",
+           "quest_append_estimate", "quest_topk", "quest_sparse_decode", "quest_select_decode",
            "quest_step_workspace_bytes", "quest_decode_step", "quest_last_error")
 
 
@@ -66,6 +66,7 @@ def load():
     lib.quest_append_estimate.argtypes = [cp, vp, vp, i32, vp, vp, vp]
     lib.quest_topk.argtypes = [cp, vp, i32, vp, vp, vp]
     lib.quest_sparse_decode.argtypes = [cp, vp, vp, i32, f32, vp, i32, vp, vp, ctypes.c_size_t, vp]
+    lib.quest_select_decode.argtypes = [cp, vp, vp, i32, f32, vp, vp, vp, i32, vp, vp, ctypes.c_size_t, vp]
     lib.quest_step_workspace_bytes.argtypes = [cp, i32, ctypes.POINTER(ctypes.c_size_t)]
     lib.quest_decode_step.argtypes = [cp, vp, vp, i32, vp, i32, f32, vp, vp, vp, vp, i32, vp, vp,
                                       ctypes.c_size_t, vp]
@@ -154,6 +155,16 @@ def quest_sparse_decode(cache: Cache, q, topk_idx, k_pages, sm_scale, out, lse=N
     _check(load().quest_sparse_decode(
         cache.ref, _ptr(q), _ptr(topk_idx), int(k_pages), float(sm_scale), _ptr(out),
         int(out.dtype == torch.float16), _ptr(lse), _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def quest_select_decode(cache: Cache, q, scores, k_pages, sm_scale, topk_idx, out, k_eff=None,
+                        lse=None, workspace=None, stream=None):
+    import torch
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().quest_select_decode(
+        cache.ref, _ptr(q), _ptr(scores), int(k_pages), float(sm_scale), _ptr(topk_idx), _ptr(k_eff),
+        _ptr(out), int(out.dtype == torch.float16), _ptr(lse), _ptr(workspace), ws_bytes,
+        _stream(stream)))
 
 
 def quest_step_workspace_bytes(cache: Cache, k_pages: int) -> int:

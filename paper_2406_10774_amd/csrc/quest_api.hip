@@ -171,6 +171,31 @@ int quest_sparse_decode(const quest_cache* cache, const void* q, const int32_t* 
                               workspace, (hipStream_t)stream);
 }
 
+int quest_select_decode(const quest_cache* cache, const void* q, const float* scores,
+                        int32_t k_pages, float sm_scale, int32_t* topk_idx, int32_t* k_eff,
+                        void* out, int32_t out_is_fp16, float* lse, void* workspace,
+                        size_t workspace_bytes, void* stream) {
+  int r = check_cache(cache, "quest_select_decode");
+  if (r != QUEST_OK) return r;
+  if (cache->k_pool == nullptr || cache->v_pool == nullptr || q == nullptr || scores == nullptr ||
+      topk_idx == nullptr || out == nullptr) {
+    set_error("quest_select_decode: k_pool, v_pool, q, scores, topk_idx and out must not be NULL");
+    return QUEST_ERR_NULL;
+  }
+  if (k_pages < 1) {
+    set_error("quest_select_decode: k_pages must be >= 1 (got %d)", k_pages);
+    return QUEST_ERR_SHAPE;
+  }
+  const size_t need = decode_workspace_bytes(*cache, k_pages);
+  if (need > 0 && (workspace == nullptr || workspace_bytes < need)) {
+    set_error("quest_select_decode: workspace of %zu bytes needed, %zu given", need,
+              workspace ? workspace_bytes : (size_t)0);
+    return QUEST_ERR_WORKSPACE;
+  }
+  return launch_select_decode(*cache, q, scores, k_pages, sm_scale, topk_idx, k_eff, out,
+                              out_is_fp16 != 0, lse, workspace, (hipStream_t)stream);
+}
+
 int quest_step_workspace_bytes(const quest_cache* cache, int32_t k_pages, size_t* out_bytes) {
   int r = check_cache(cache, "quest_step_workspace_bytes");
   if (r != QUEST_OK) return r;

@@ -465,13 +465,13 @@ int launch_decode(const quest_cache& c, const void* q, const int32_t* topk_idx, 
       hipLaunchKernelGGL((decode_split_kernel<2, 1, kSelWaves, I>), grid, block, 0, s, a);   \
     else                                                                                     \
       hipLaunchKernelGGL((decode_split_kernel<4, 1, kSelWaves, I>), grid, block, 0, s, a);   \
-    return check_launch("quest_decode_step");                                                \
+    return check_launch("quest_select_decode");                                              \
   }
     QUEST_SELECT_CASE(2)
     QUEST_SELECT_CASE(5)
     QUEST_SELECT_CASE(8)
 #undef QUEST_SELECT_CASE
-    set_error("quest_decode_step: internal: no selecting kernel for max_pages_per_seq = %d", mp);
+    set_error("quest_select_decode: internal: no selecting kernel for max_pages_per_seq = %d", mp);
     return QUEST_ERR_SHAPE;
   }
 #define QUEST_DECODE_LAUNCH(L, G) \
@@ -510,8 +510,12 @@ bool select_decode_supported(const quest_cache& c, int k_pages) {
 int launch_select_decode(const quest_cache& c, const void* q, const float* scores, int k_pages,
                          float sm_scale, int32_t* topk_idx, int32_t* k_eff, void* out,
                          int out_is_fp16, float* lse, void* workspace, hipStream_t s) {
-  return launch_decode(c, q, nullptr, scores, topk_idx, k_eff, k_pages, sm_scale, out, out_is_fp16,
-                       lse, workspace, s);
+  if (select_decode_supported(c, k_pages))
+    return launch_decode(c, q, nullptr, scores, topk_idx, k_eff, k_pages, sm_scale, out, out_is_fp16,
+                         lse, workspace, s);
+  const int r = launch_topk(c, scores, k_pages, topk_idx, k_eff, s);
+  if (r != QUEST_OK) return r;
+  return launch_sparse_decode(c, q, topk_idx, k_pages, sm_scale, out, out_is_fp16, lse, workspace, s);
 }
 
 }  // namespace quest

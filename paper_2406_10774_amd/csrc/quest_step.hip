@@ -2,9 +2,10 @@
 // criticality estimate, Top-K selection and sparse attention (Algorithm 1 and
 // Figure 5 of arXiv 2406.10774), as two launches:
 //   1. quest_append_estimate (quest_estimate without a new token): the metadata stream;
-//   2. the attention kernel with the selection inside (quest_decode.hip): every
-//      work-group selects the pages of its head itself from the scores, keeps the
-//      list in LDS and attends over its slice; one of them writes the list out.
+//   2. quest_select_decode: the attention kernel with the selection inside
+//      (quest_decode.hip): every work-group selects the pages of its head itself from
+//      the scores, keeps the list in LDS and attends over its slice; one of them writes
+//      the list out.
 // Same arithmetic as the separate calls (shared device cores): metadata, scores
 // and the page list are bit-equal to theirs.  When a row of scores or the list is
 // too long for that, the selection runs as its own launch (three launches).
@@ -30,12 +31,8 @@ int launch_decode_step(const quest_cache& c, const void* k_new, const void* v_ne
   int r = k_new ? launch_append_estimate(c, k_new, v_new, k_pool_write, q, scores, s)
                 : launch_estimate(c, q, scores, s);
   if (r != QUEST_OK) return r;
-  if (select_decode_supported(c, k_pages))
-    return launch_select_decode(c, q, scores, k_pages, sm_scale, topk_idx, k_eff, out, out_is_fp16,
-                                lse, workspace, s);
-  r = launch_topk(c, scores, k_pages, topk_idx, k_eff, s);
-  if (r != QUEST_OK) return r;
-  return launch_sparse_decode(c, q, topk_idx, k_pages, sm_scale, out, out_is_fp16, lse, workspace, s);
+  return launch_select_decode(c, q, scores, k_pages, sm_scale, topk_idx, k_eff, out, out_is_fp16, lse,
+                              workspace, s);
 }
 
 }  // namespace quest

@@ -86,6 +86,24 @@ class Layer:
         o = out.cpu().numpy() if not fp16_out else self.np16(out)
         return o, (lse.cpu().numpy() if want_lse else None)
 
+    def select_decode(self, q, k_pages, scores=None, sm_scale=None):
+        """Selection and attention in one call, from the scores of the last estimate (or
+        the given ones).  Returns (topk_idx, k_eff, out, lse)."""
+        torch = self.torch
+        sm_scale = 1.0 / math.sqrt(self.D) if sm_scale is None else sm_scale
+        sc = self.scores if scores is None else torch.from_numpy(
+            np.ascontiguousarray(scores, dtype=np.float32)).to(self.dev)
+        ws_bytes = Q.quest_workspace_bytes(self.cache, k_pages)
+        ws = torch.zeros(max(ws_bytes, 4) // 4, dtype=torch.float32, device=self.dev)
+        idx = torch.full((self.B, self.H, k_pages), -7, dtype=torch.int32, device=self.dev)
+        keff = torch.full((self.B,), -7, dtype=torch.int32, device=self.dev)
+        out = torch.full((self.B, self.Hq, self.D), float("nan"), dtype=torch.float32, device=self.dev)
+        lse = torch.full((self.B, self.Hq), float("nan"), dtype=torch.float32, device=self.dev)
+        Q.quest_select_decode(self.cache, self.half(q), sc, k_pages, sm_scale, idx, out, k_eff=keff,
+                              lse=lse, workspace=ws)
+        torch.cuda.synchronize()
+        return idx.cpu().numpy(), keff.cpu().numpy(), out.cpu().numpy(), lse.cpu().numpy()
+
     def step(self, k_new, v_new, q, k_pages, sm_scale=None, write=True):
         """The whole decode step through the one-call entry point."""
         torch = self.torch

@@ -79,6 +79,13 @@ def test_null_and_range_arguments():
     assert lib.quest_sparse_decode(r, 0x1000, 0x1000, 128, 1.0, 0x1000, 0, None, None, 0,
                                    None) == -4
     assert b"workspace" in lib.quest_last_error()
+    # selection + attention from given scores: same rules
+    assert lib.quest_select_decode(r, 0x1000, None, 128, 1.0, 0x1000, None, 0x1000, 0, None, 0x1000,
+                                   1 << 30, None) == -1              # scores
+    assert lib.quest_select_decode(r, 0x1000, 0x1000, 0, 1.0, 0x1000, None, 0x1000, 0, None, 0x1000,
+                                   1 << 30, None) == -2              # k_pages < 1
+    assert lib.quest_select_decode(r, 0x1000, 0x1000, 128, 1.0, 0x1000, None, 0x1000, 0, None, None,
+                                   0, None) == -4
 
 
 def test_product_package_does_not_import_the_oracle(repo_root):

@@ -277,6 +277,29 @@ def test_sparse_decode_against_oracle(ragged):
     assert (np.abs(got16.astype(np.float64) - w16.astype(np.float64)) <= ulp).all()
 
 
+@pytest.mark.parametrize("flags", [0, 1, 2, 12])
+def test_select_decode_is_topk_then_sparse_decode(ragged, flags):
+    """quest_select_decode on given scores: the list of quest_topk bit for bit (ties, rows
+    shorter than K, one-page sequences), the attention of quest_sparse_decode over it."""
+    from gpu_util import Layer
+    w, table, N, k_pool, v_pool, q, lens, _ = ragged
+    layer = Layer(k_pool, v_pool, table, lens, flags=flags)
+    layer.build_meta()
+    rng = np.random.default_rng(flags)
+    scale = 1 / math.sqrt(w.head_dim)
+    for k_pages in (1, 3, 24, 64, 300):
+        sc = layer.estimate(q)
+        if k_pages == 3:                               # ties at the threshold
+            sc = np.round(sc / 8) * 8
+        sc = np.where(np.isfinite(sc), sc, 0).astype(np.float32)
+        want_idx, want_keff = layer.topk(k_pages, scores=sc)
+        idx, keff, out, lse = layer.select_decode(q, k_pages, scores=sc)
+        assert np.array_equal(idx, want_idx) and np.array_equal(keff, want_keff), k_pages
+        want, want_lse = O.sparse_decode(k_pool, v_pool, q, table, lens, idx, scale)
+        assert np.abs(out - want).max() <= ATTN_TOL, k_pages
+        assert np.abs(lse - want_lse).max() <= ATTN_TOL, k_pages
+
+
 def test_agreement_tells_a_single_wrong_page(ragged):
     """How sharp the comparison is: the stated bar for attention is 2e-3, the observed
     distance to the oracle is fp32 rounding noise.  A list that is wrong in its least
