@@ -292,7 +292,7 @@ def main():
         "value": round(us_step, 3), "unit": "us/layer-step",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(us_step * 1e-3, 6), "higher_is_better": False, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f16 in / f32 accumulate", "data": "synthetic",
+        "vs_baseline": None, "dtype": "f32", "storage_dtype": "f16", "data": "synthetic",
         "config": {"workload": w.name, "batch": B, "heads": Hq, "kv_heads": H, "head_dim": D,
                    "page_size": S,
                    "context": int(lens0.max()), "token_budget": w.token_budget, "k_pages": K,
