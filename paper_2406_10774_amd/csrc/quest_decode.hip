@@ -44,7 +44,7 @@ constexpr int kSelListCap = 2048;
 #ifdef QUEST_STEP_TRACE
 #define DEC_TRACE(slot)                                                                  \
   do {                                                                                   \
-    if (threadIdx.x == 0 && a.trace) a.trace[(size_t)blockIdx.x * 16 + (slot)] = wall_clock64(); \
+    if (threadIdx.x == 0 && a.trace) a.trace[((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 16 + (slot)] = wall_clock64(); \
   } while (0)
 #else
 #define DEC_TRACE(slot) \
@@ -89,8 +89,8 @@ struct DecodeArgs {
 #endif
 };
 
-// Grid is one-dimensional and die-aware: work-groups whose ids are equal modulo
-// 8 run on the same die (round-robin placement), and
+// The grid is die-aware: work-groups whose linear ids are equal modulo 8 run on the
+// same die (round-robin placement; grid.x is a multiple of 8), and
 // all splits of one (sequence, head) are given ids with the same i % 8, so
 // their partial results meet in one L2 and the last split to finish can merge
 // them without a second launch and without device-wide cache maintenance.
@@ -117,15 +117,20 @@ __global__ __launch_bounds__(kWaves* kWave) void decode_split_kernel(const Decod
   __shared__ TopkShared<kWaves * kWave> sm_topk;
   __shared__ int32_t sm_list[kSelItems > 0 ? kSelListCap : 1];
 
+  // blockIdx.x = slot + 8 * split, blockIdx.y = group of 8 items: the linear work-group
+  // id is slot + 8 * (split + splits * blockIdx.y).  The usual shapes (one sequence, one
+  // work-group per KV head) are taken apart without integer divisions: they sit in
+  // front of the first load of every work-group.
   const int slot = blockIdx.x & 7;
-  const int rank = blockIdx.x >> 3;
-  const int split = rank % a.splits;
-  const int item = (rank / a.splits) * 8 + slot;  // (sequence, KV head, kG query heads of its group)
-  const int subs = a.group / kG;
-  if (item >= a.batch * a.kv_heads * subs) return;
-  const int b = item / (a.kv_heads * subs);
-  const int hk = (item - b * a.kv_heads * subs) / subs;  // the KV head: its pages, its page list
-  const int h = hk * a.group + (item % subs) * kG;        // first query head served here
+  const int split = blockIdx.x >> 3;
+  const int item = blockIdx.y * 8 + slot;  // (sequence, KV head, kG query heads of its group)
+  const int subs = a.group / kG;           // work-groups per KV head and split: 1 without groups
+  const int per_seq = a.kv_heads * subs;
+  if (item >= a.batch * per_seq) return;
+  const int b = a.batch == 1 ? 0 : item / per_seq;
+  const int in_seq = item - b * per_seq;
+  const int hk = subs == 1 ? in_seq : in_seq / subs;  // the KV head: its pages, its page list
+  const int h = hk * a.group + (in_seq - hk * subs) * kG;  // first query head served here
   const size_t bh = (size_t)b * a.num_heads + h;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = lane_id();
@@ -151,7 +156,7 @@ __global__ __launch_bounds__(kWaves* kWave) void decode_split_kernel(const Decod
     const bool writer = split == 0 && h == hk * a.group;  // one work-group per list writes it out
     int32_t* out_row = a.topk_out + row * a.k_pages;
 #ifdef QUEST_STEP_TRACE
-    if (threadIdx.x == 0) sm_topk.trace = a.trace ? a.trace + (size_t)blockIdx.x * 16 : nullptr;
+    if (threadIdx.x == 0) sm_topk.trace = a.trace ? a.trace + ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 16 : nullptr;
 #endif
     topk_block_put<kWaves * kWave, (kSelItems > 0 ? kSelItems : 1)>(
         sm_topk, a.scores + row * a.max_pages, a.seq_lens + b, a.max_pages, a.k_pages,
@@ -455,7 +460,11 @@ int launch_decode(const quest_cache& c, const void* q, const int32_t* topk_idx, 
   a.part_ml = a.part_acc ? a.part_acc + n_part * kHeadDim : nullptr;
   const int kg = heads_per_group(c, a.k_pages);
   const long items8 = ((long)c.batch * c.num_heads / kg + 7) / 8;
-  const dim3 grid((unsigned)(items8 * 8 * a.splits));
+  if (items8 > 65535) {
+    set_error("quest_sparse_decode: batch * heads = %ld exceeds the launch limit", items8 * 8);
+    return QUEST_ERR_SHAPE;
+  }
+  const dim3 grid((unsigned)(8 * a.splits), (unsigned)items8);
   if (select) {
     const int mp = c.max_pages_per_seq;
     const dim3 block(kSelWaves * kWave);
