@@ -135,15 +135,15 @@ def test_topk_exact_on_shared_scores(ragged, k_pages):
     assert np.array_equal(got, want)
 
 
-@pytest.mark.parametrize("max_pages,lens", [
-    (4096, (16 * 4096, 16 * 3000 + 1)),        # 512 threads x 8 keys
-    (8192, (16 * 8192, 16 * 5000)),            # 512 x 16
-    (12288, (16 * 12288 - 3, 16 * 9000)),      # 1024 x 12
-    (32769, (16 * 32769, 16 * 20000 + 9)),     # 1024 x 33
-    (65535, (16 * 65535, 16 * 40000)),         # 1024 x 64
-    (70000, (16 * 70000, 16 * 66000)),         # rows too long for registers: keys re-read from memory
+@pytest.mark.parametrize("max_pages,lens,per_thread", [
+    (4096, (16 * 4096, 16 * 3000 + 1), 8),         # 512 threads x 8 keys
+    (8192, (16 * 8192, 16 * 5000), 16),            # 512 x 16
+    (12288, (16 * 12288 - 3, 16 * 9000), 12),      # 1024 x 12
+    (32769, (16 * 32769, 16 * 20000 + 9), 33),     # 1024 x 33
+    (65535, (16 * 65535, 16 * 40000), 64),         # 1024 x 64
+    (70000, (16 * 70000, 16 * 66000), 1),          # rows too long for registers: keys re-read from memory
 ])
-def test_topk_long_rows(max_pages, lens):
+def test_topk_long_rows(max_pages, lens, per_thread):
     """Every register-tiling variant of the selection kernel, scores only."""
     import torch
     from paper_2406_10774_amd import binding as Q
@@ -154,6 +154,9 @@ def test_topk_long_rows(max_pages, lens):
     sc[0, 1] = np.round(sc[0, 1])                      # ties
     sc[1, 2] = 7.0                                     # all equal
     sc[1, 0, ::3] *= -1                                # mixed signs: no common top byte
+    # the first key of every thread is large and all others are small (a pattern aligned
+    # with the threads' shares of the row)
+    sc[0, 2, ::per_thread] += 1e6
     lens = np.array(lens, np.int32)
     # placeholder pools: the selection kernel never touches them
     dummy = torch.zeros((1, H, S, 128), dtype=torch.float16, device=dev)
