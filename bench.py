@@ -213,7 +213,7 @@ def main():
     if one_call:
         us_step, us_step_events = two_us, two_us_events
         calls = ("quest_decode_step (two launches: estimate; selection + attention)" if selects_inside
-                 else "quest_decode_step (three launches inside one call)")
+                 else "quest_decode_step (one call; estimate, selection and attention as launches of their own)")
 
     g_dense = capture(dense_step, timed)
     g_dense.replay()

@@ -117,11 +117,15 @@ typedef struct quest_cache {
                                  else a divisor of num_heads (see below)     */
 } quest_cache;
 
-/* Bytes of device workspace quest_sparse_decode needs for this cache and
- * k_pages (k_pages <= 0: the dense path over all pages).  Pure host function.
+/* Bytes of device workspace quest_sparse_decode, quest_select_decode and
+ * quest_decode_step need for this cache and k_pages (k_pages <= 0: the dense
+ * path of quest_sparse_decode over all pages).  Pure host function.
  * The workspace holds one arrival counter per (sequence, head) and the split-K
  * partial results (running max, denominator and un-normalised accumulator of
- * each split).  *out_bytes may be 0.
+ * each split); for rows of 16384 pages or more also the candidates of the
+ * two-stage selection that quest_select_decode and quest_decode_step then use
+ * (the best k_pages of every 4096-page chunk of a row, when there are at most
+ * 8192 of them per row).  *out_bytes may be 0.
  * A workspace must be zero-filled once, after it is allocated and before its
  * first use (e.g. hipMemset); every call leaves the counters at zero again, so
  * the same workspace serves later calls, sparse or dense, on the same cache
@@ -196,7 +200,9 @@ int quest_sparse_decode(const quest_cache* cache, const void* q, const int32_t* 
  * work-group first selects the pages of its (sequence, KV head) from the scores
  * and keeps the list in on-chip memory, when k_pages <= 2048 and
  * max_pages_per_seq <= 4096 and QUEST_FLAG_SEPARATE_LAUNCHES is not set; else
- * the two launches.  workspace: as for quest_sparse_decode with this k_pages. */
+ * the selection and the attention as launches of their own (the selection in
+ * two stages for very long rows, see quest_workspace_bytes).
+ * workspace: at least quest_workspace_bytes(cache, k_pages). */
 int quest_select_decode(const quest_cache* cache, const void* q, const float* scores,
                         int32_t k_pages, float sm_scale, int32_t* topk_idx, int32_t* k_eff,
                         void* out, int32_t out_is_fp16, float* lse, void* workspace,
@@ -215,8 +221,9 @@ int quest_select_decode(const quest_cache* cache, const void* q, const float* sc
  * allocation (same rule as for quest_sparse_decode; one buffer may serve both
  * calls); calls sharing a workspace must not overlap in time.
  * The call enqueues the estimate, then what quest_select_decode enqueues: two
- * launches when k_pages <= 2048 and max_pages_per_seq <= 4096 and
- * QUEST_FLAG_SEPARATE_LAUNCHES is not set, else three. */
+ * launches in all when k_pages <= 2048 and max_pages_per_seq <= 4096 and
+ * QUEST_FLAG_SEPARATE_LAUNCHES is not set, else three (four with the two-stage
+ * selection of very long rows). */
 int quest_step_workspace_bytes(const quest_cache* cache, int32_t k_pages, size_t* out_bytes);
 int quest_decode_step(const quest_cache* cache, const void* k_new, const void* v_new,
                       int32_t k_pool_write, const void* q, int32_t k_pages, float sm_scale,

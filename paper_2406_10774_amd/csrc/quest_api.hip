@@ -76,7 +76,8 @@ int quest_workspace_bytes(const quest_cache* cache, int32_t k_pages, size_t* out
     set_error("quest_workspace_bytes: out_bytes is NULL");
     return QUEST_ERR_NULL;
   }
-  *out_bytes = decode_workspace_bytes(*cache, k_pages);
+  // with a page list: enough for quest_select_decode and quest_decode_step as well
+  *out_bytes = k_pages > 0 ? step_workspace_bytes(*cache, k_pages) : decode_workspace_bytes(*cache, 0);
   return QUEST_OK;
 }
 
@@ -186,7 +187,7 @@ int quest_select_decode(const quest_cache* cache, const void* q, const float* sc
     set_error("quest_select_decode: k_pages must be >= 1 (got %d)", k_pages);
     return QUEST_ERR_SHAPE;
   }
-  const size_t need = decode_workspace_bytes(*cache, k_pages);
+  const size_t need = step_workspace_bytes(*cache, k_pages);
   if (need > 0 && (workspace == nullptr || workspace_bytes < need)) {
     set_error("quest_select_decode: workspace of %zu bytes needed, %zu given", need,
               workspace ? workspace_bytes : (size_t)0);

@@ -48,6 +48,11 @@ int launch_append_estimate(const quest_cache& c, const void* k_new, const void* 
                            int k_pool_write, const void* q, float* scores, hipStream_t s);
 int launch_topk(const quest_cache& c, const float* scores, int k_pages, int32_t* topk_idx,
                 int32_t* k_eff, hipStream_t s);
+// Scratch for the two-stage selection of very long rows (0: not used for this shape), and
+// the selection itself; the scratch need not be initialised.
+size_t topk_scratch_bytes(const quest_cache& c, int k_pages);
+int launch_topk_chunked(const quest_cache& c, const float* scores, int k_pages, int32_t* topk_idx,
+                        int32_t* k_eff, void* scratch, hipStream_t s);
 int decode_num_splits(const quest_cache& c, int k_pages);
 size_t decode_workspace_bytes(const quest_cache& c, int k_pages);
 int launch_sparse_decode(const quest_cache& c, const void* q, const int32_t* topk_idx, int k_pages,

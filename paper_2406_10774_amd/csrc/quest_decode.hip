@@ -164,7 +164,8 @@ __global__ __launch_bounds__(kWaves* kWave) void decode_split_kernel(const Decod
           sm_list[pos] = page;
           if (writer) out_row[pos] = page;
         },
-        (writer && hk == 0 && a.k_eff != nullptr) ? a.k_eff + b : nullptr, a.page_shift, a.policy);
+        (writer && hk == 0 && a.k_eff != nullptr) ? a.k_eff + b : nullptr,
+        WholeRow{a.page_shift, a.policy});
     __syncthreads();
     DEC_TRACE(6);
   }
@@ -522,7 +523,11 @@ int launch_select_decode(const quest_cache& c, const void* q, const float* score
   if (select_decode_supported(c, k_pages))
     return launch_decode(c, q, nullptr, scores, topk_idx, k_eff, k_pages, sm_scale, out, out_is_fp16,
                          lse, workspace, s);
-  const int r = launch_topk(c, scores, k_pages, topk_idx, k_eff, s);
+  // very long rows: selection in two stages, candidates behind the attention's workspace
+  const int r = topk_scratch_bytes(c, k_pages) > 0
+                    ? launch_topk_chunked(c, scores, k_pages, topk_idx, k_eff,
+                                          (char*)workspace + decode_workspace_bytes(c, k_pages), s)
+                    : launch_topk(c, scores, k_pages, topk_idx, k_eff, s);
   if (r != QUEST_OK) return r;
   return launch_sparse_decode(c, q, topk_idx, k_pages, sm_scale, out, out_is_fp16, lse, workspace, s);
 }

@@ -20,7 +20,7 @@
 namespace quest {
 
 size_t step_workspace_bytes(const quest_cache& c, int k_pages) {
-  return decode_workspace_bytes(c, k_pages);
+  return decode_workspace_bytes(c, k_pages) + topk_scratch_bytes(c, k_pages);
 }
 
 int launch_decode_step(const quest_cache& c, const void* k_new, const void* v_new, int k_pool_write,

@@ -133,6 +133,89 @@ __global__ __launch_bounds__(kBigThreads) void topk_big_kernel(
   }
 }
 
+// ---- Selection in two stages for very long rows.  One work-group per row is bound by
+// what one compute unit can issue (about 0.75 us per key and thread at 1024 threads);
+// here the row is cut into chunks of kChunkPages pages, a work-group per chunk selects
+// the chunk's own best K pages (the K best of the row are among them, ties included:
+// fewer than K pages of the chunk rank above any of them), and a second launch selects
+// among the candidates.  Candidates are stored densely in page order (every chunk
+// before the last non-empty one is full and yields exactly k_pages of them), so
+// positions in the candidate row order like pages do: equal scores still go to the
+// lower page, page 0 is candidate 0 and the newest page is the last candidate whenever
+// the policy flags keep them in their chunks.
+constexpr int kChunkThreads = 512;
+constexpr int kChunkItems = 8;
+constexpr int kChunkPages = kChunkThreads * kChunkItems;
+
+struct ChunkOfRow {
+  int page_shift, policy, chunk;
+  __device__ __forceinline__ RowShape operator()(int seq_len) const {
+    const int pages = (seq_len + (1 << page_shift) - 1) >> page_shift;
+    const int local = min(max(pages - chunk * kChunkPages, 0), kChunkPages);
+    int pol = 0;
+    if (chunk == 0) pol |= policy & QUEST_FLAG_KEEP_FIRST_PAGE;
+    if (local > 0 && (chunk + 1) * kChunkPages >= pages) pol |= policy & QUEST_FLAG_KEEP_NEWEST_PAGE;
+    return {local, pol};
+  }
+};
+
+__global__ __launch_bounds__(kChunkThreads) void topk_chunk_kernel(
+    const float* __restrict__ scores, const int32_t* __restrict__ seq_lens,
+    float* __restrict__ cand_score, int32_t* __restrict__ cand_page, int num_heads, int max_pages,
+    int k_pages, int num_chunks, int page_shift, int policy) {
+  __shared__ TopkShared<kChunkThreads> sm;
+#ifdef QUEST_STEP_TRACE
+  if (threadIdx.x == 0) sm.trace = nullptr;
+#endif
+  const int chunk = blockIdx.x;
+  const int h = blockIdx.y;
+  const int b = blockIdx.z;
+  const size_t bh = (size_t)b * num_heads + h;
+  const float* row = scores + bh * max_pages + (size_t)chunk * kChunkPages;
+  const size_t at = (bh * num_chunks + chunk) * k_pages;
+  float* out_score = cand_score + at;
+  int32_t* out_page = cand_page + at;
+  topk_block_put<kChunkThreads, kChunkItems>(
+      sm, row, seq_lens + b, min(kChunkPages, max_pages - chunk * kChunkPages), k_pages,
+      [=](int pos, int page) {
+        if (page >= 0) {
+          out_page[pos] = page + chunk * kChunkPages;
+          out_score[pos] = row[page];
+        }
+      },
+      nullptr, ChunkOfRow{page_shift, policy, chunk});
+}
+
+struct CandidateRow {
+  int page_shift, policy, k_pages;
+  __device__ __forceinline__ RowShape operator()(int seq_len) const {
+    const int pages = (seq_len + (1 << page_shift) - 1) >> page_shift;
+    const int full = pages / kChunkPages;
+    return {full * k_pages + min(k_pages, pages - full * kChunkPages), policy};
+  }
+};
+
+template <int kThreads, int kItems>
+__global__ __launch_bounds__(kThreads) void topk_candidates_kernel(
+    const float* __restrict__ cand_score, const int32_t* __restrict__ cand_page,
+    const int32_t* __restrict__ seq_lens, int32_t* __restrict__ topk_idx,
+    int32_t* __restrict__ k_eff, int num_heads, int row_len, int k_pages, int page_shift,
+    int policy) {
+  __shared__ TopkShared<kThreads> sm;
+#ifdef QUEST_STEP_TRACE
+  if (threadIdx.x == 0) sm.trace = nullptr;
+#endif
+  const int h = blockIdx.x;
+  const int b = blockIdx.y;
+  const size_t bh = (size_t)b * num_heads + h;
+  const int32_t* pages = cand_page + bh * row_len;
+  int32_t* out = topk_idx + bh * k_pages;
+  topk_block_put<kThreads, kItems>(
+      sm, cand_score + bh * row_len, seq_lens + b, row_len, k_pages,
+      [=](int pos, int cand) { out[pos] = cand >= 0 ? pages[cand] : -1; },
+      (h == 0 && k_eff != nullptr) ? k_eff + b : nullptr, CandidateRow{page_shift, policy, k_pages});
+}
+
 template <int kThreads, int kItems>
 int launch_one(const quest_cache& c, const float* scores, int k_pages, int32_t* topk_idx,
                int32_t* k_eff, hipStream_t s) {
@@ -172,6 +255,50 @@ int launch_topk(const quest_cache& c, const float* scores, int k_pages, int32_t*
                      c.seq_lens, topk_idx, k_eff, kv_heads(c), c.max_pages_per_seq, k_pages,
                      page_shift_of(c.page_size), c.flags);
   return check_launch("quest_topk");
+}
+
+// Rows from kChunkedFromPages pages on are selected in two stages when the caller
+// brings scratch memory for the candidates (quest_select_decode, quest_decode_step).
+constexpr int kChunkedFromPages = 16384;
+constexpr int kMaxCandidates = 512 * 16;
+
+static int num_chunks(const quest_cache& c) {
+  return (c.max_pages_per_seq + kChunkPages - 1) / kChunkPages;
+}
+
+size_t topk_scratch_bytes(const quest_cache& c, int k_pages) {
+  const long cand = (long)num_chunks(c) * k_pages;
+  if (c.max_pages_per_seq < kChunkedFromPages || k_pages < 1 || k_pages > kChunkPages ||
+      cand > kMaxCandidates || 2 * cand > c.max_pages_per_seq)
+    return 0;
+  return (size_t)c.batch * kv_heads(c) * cand * (sizeof(float) + sizeof(int32_t));
+}
+
+int launch_topk_chunked(const quest_cache& c, const float* scores, int k_pages, int32_t* topk_idx,
+                        int32_t* k_eff, void* scratch, hipStream_t s) {
+  const int chunks = num_chunks(c);
+  const int row_len = chunks * k_pages;
+  float* cand_score = (float*)scratch;
+  int32_t* cand_page = (int32_t*)(cand_score + (size_t)c.batch * kv_heads(c) * row_len);
+  hipLaunchKernelGGL(topk_chunk_kernel, dim3(chunks, kv_heads(c), c.batch), dim3(kChunkThreads), 0, s,
+                     scores, c.seq_lens, cand_score, cand_page, kv_heads(c), c.max_pages_per_seq,
+                     k_pages, chunks, page_shift_of(c.page_size), c.flags);
+  int r = check_launch("quest_select_decode");
+  if (r != QUEST_OK) return r;
+#define QUEST_CAND_CASE(I)                                                                       \
+  if (row_len <= 512 * (I)) {                                                                    \
+    hipLaunchKernelGGL((topk_candidates_kernel<512, I>), dim3(kv_heads(c), c.batch), dim3(512), 0, \
+                       s, cand_score, cand_page, c.seq_lens, topk_idx, k_eff, kv_heads(c), row_len, \
+                       k_pages, page_shift_of(c.page_size), c.flags);                            \
+    return check_launch("quest_select_decode");                                                  \
+  }
+  QUEST_CAND_CASE(2)
+  QUEST_CAND_CASE(5)
+  QUEST_CAND_CASE(8)
+  QUEST_CAND_CASE(16)
+#undef QUEST_CAND_CASE
+  set_error("quest_select_decode: internal: %d candidates per row", row_len);
+  return QUEST_ERR_SHAPE;
 }
 
 }  // namespace quest

@@ -123,17 +123,29 @@ struct TopkShared {
   } while (0)
 #endif
 
+// What a row of scores is, given the sequence length: its number of valid entries and
+// which of them are kept whatever their score (QUEST_FLAG_KEEP_* bits).
+struct RowShape {
+  int num_pages, policy;
+};
+// The row holds the scores of all pages of the sequence.
+struct WholeRow {
+  int page_shift, policy;
+  __device__ __forceinline__ RowShape operator()(int seq_len) const {
+    return {(seq_len + (1 << page_shift) - 1) >> page_shift, policy};
+  }
+};
+
 // Selection for one row of scores by one work-group of kThreads threads (all of
-// them must call).
-// put(position, page) receives the list: positions 0 .. k_pages-1, pages
+// them must call).  shape(seq_len) describes the row (it has room for max_pages
+// entries); put(position, page) receives the list: positions 0 .. k_pages-1, pages
 // ascending, -1 past the K_b selected ones.
-template <int kThreads, int kItems, class Put>
+template <int kThreads, int kItems, class Put, class Shape>
 __device__ __forceinline__ void topk_block_put(TopkShared<kThreads>& sm,
                                                const float* __restrict__ row,
                                                const int32_t* __restrict__ seq_len_ptr,
                                                int max_pages, int k_pages, Put put,
-                                               int32_t* __restrict__ k_eff_slot, int page_shift,
-                                               int policy) {
+                                               int32_t* __restrict__ k_eff_slot, Shape shape) {
   constexpr int kWaves = kThreads / kWave;
   constexpr int kCopies0 = hist_copies0(kItems);
   uint32_t(&hist)[kMaxHistCopies0 + 3][256] = sm.hist;
@@ -158,7 +170,8 @@ __device__ __forceinline__ void topk_block_put(TopkShared<kThreads>& sm,
 
   for (int i = tid; i < (kCopies0 + 3) * 256; i += kThreads) (&hist[0][0])[i] = 0;
 
-  const int num_pages = (seq_len + (1 << page_shift) - 1) >> page_shift;
+  const RowShape row_shape = shape(seq_len);
+  const int num_pages = row_shape.num_pages;
   const int K = min(k_pages, num_pages);
   if (tid == 0 && k_eff_slot != nullptr) *k_eff_slot = K;
   if (K == num_pages) {  // everything is selected: identity list, padded with -1
@@ -169,7 +182,7 @@ __device__ __forceinline__ void topk_block_put(TopkShared<kThreads>& sm,
   // Pages that are kept whatever their score rank above every score and, like
   // equal scores, by page index: they stay out of the histograms, take their
   // places off the count, and are emitted with the keys above the threshold.
-  const ForcedPages forced = forced_pages(policy, num_pages);
+  const ForcedPages forced = forced_pages(row_shape.policy, num_pages);
   if (forced.count >= K) {  // K is 1 or 2 here: the list is the forced pages, lowest first
     if (tid == 0) {
       put(0, forced.first ? 0 : num_pages - 1);
@@ -286,7 +299,7 @@ __device__ __forceinline__ void topk_block(TopkShared<kThreads>& sm, const float
                                            int policy) {
   topk_block_put<kThreads, kItems>(
       sm, row, seq_len_ptr, max_pages, k_pages, [out](int pos, int page) { out[pos] = page; },
-      k_eff_slot, page_shift, policy);
+      k_eff_slot, WholeRow{page_shift, policy});
 }
 
 #endif  // __HIPCC__

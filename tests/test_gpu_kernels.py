@@ -173,6 +173,47 @@ def test_topk_long_rows(max_pages, lens, per_thread):
         assert np.array_equal(idx.cpu().numpy(), want), (max_pages, k_pages)
 
 
+@pytest.mark.parametrize("policy", [0, 12])
+@pytest.mark.parametrize("max_pages,lens", [
+    (16384, (16 * 16384, 16 * 4096, 16 * 9000 + 3, 5)),     # 4 chunks; rows ending on / inside a chunk
+    (32769, (16 * 32769, 16 * 32768, 16 * 200, 16 * 28673 - 1)),
+])
+def test_select_decode_very_long_rows(policy, max_pages, lens):
+    """quest_select_decode on rows from 16384 pages on selects in two stages (the best K of
+    every 4096-page chunk, then the best K of those) with scratch behind the attention's
+    workspace: the list must be that of quest_topk / the oracle, ties and forced pages
+    included.  Every logical page maps to the one physical page here: only the list and
+    K_b are checked."""
+    import torch
+    from paper_2406_10774_amd import binding as Q
+    B, H, S = len(lens), 2, 16
+    dev = "cuda:0"
+    rng = np.random.default_rng(max_pages + policy)
+    sc = (rng.standard_normal((B, H, max_pages)) * 30 + 200).astype(np.float32)
+    sc[0, 1] = np.round(sc[0, 1] / 20) * 20            # heavy ties across chunks
+    sc[1, 0] = 7.0                                     # all equal
+    sc[2, 1, 4090:4100] += 500                         # winners on both sides of a chunk border
+    lens = np.array(lens, np.int32)
+    pools = torch.randn((1, H, S, 128), dtype=torch.float16, device=dev)
+    meta = torch.zeros((H, 1, 2, 128), dtype=torch.float16, device=dev)
+    pt = torch.zeros((B, max_pages), dtype=torch.int32, device=dev)
+    cache = Q.Cache(pools, pools, meta, pt, torch.from_numpy(lens).to(dev), flags=policy)
+    scd = torch.from_numpy(sc).to(dev)
+    q = torch.randn((B, H, 128), dtype=torch.float16, device=dev)
+    for k_pages in (1, 2, 256, 700, 1024):             # 1024: too many candidates, one stage
+        ws = torch.zeros(max(Q.quest_workspace_bytes(cache, k_pages), 4) // 4, dtype=torch.int32,
+                         device=dev)
+        idx = torch.full((B, H, k_pages), -7, dtype=torch.int32, device=dev)
+        keff = torch.full((B,), -7, dtype=torch.int32, device=dev)
+        out = torch.zeros((B, H, 128), dtype=torch.float32, device=dev)
+        Q.quest_select_decode(cache, q, scd, k_pages, 0.1, idx, out, k_eff=keff, workspace=ws)
+        want, want_keff = O.topk(sc, lens, S, k_pages, keep_first=bool(policy & 4),
+                                 keep_newest=bool(policy & 8))
+        assert np.array_equal(keff.cpu().numpy(), want_keff), k_pages
+        assert np.array_equal(idx.cpu().numpy(), want), (max_pages, policy, k_pages)
+        assert torch.isfinite(out).all()
+
+
 @pytest.mark.parametrize("max_pages", [700, 3000, 6000])
 def test_topk_key_ranges(max_pages):
     """Rows whose keys span very different ranges (the selection works on keys relative to
