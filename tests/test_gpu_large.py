@@ -74,7 +74,8 @@ def test_config3_ragged_batch16():
 
 
 def test_config4_512k_context():
-    chain_at_full_size(synth.workload(4), k_pages_list=(256,), steps=1, use_step_call=False)
+    # through the one-call step: rows of 32769 pages are selected in two stages there
+    chain_at_full_size(synth.workload(4), k_pages_list=(256,), steps=1, use_step_call=True)
 
 
 @pytest.mark.parametrize("S", [8, 64])
