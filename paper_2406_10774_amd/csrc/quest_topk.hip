@@ -243,6 +243,7 @@ int launch_topk(const quest_cache& c, const float* scores, int k_pages, int32_t*
   QUEST_TOPK_CASE(512, 10);
   QUEST_TOPK_CASE(512, 12);
   QUEST_TOPK_CASE(512, 16);
+  QUEST_TOPK_CASE(512, 20);
   // up to 65536 pages (the packed prefix counts hold 16 bits each)
   QUEST_TOPK_CASE(1024, 12);
   QUEST_TOPK_CASE(1024, 17);

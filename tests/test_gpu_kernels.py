@@ -138,6 +138,7 @@ def test_topk_exact_on_shared_scores(ragged, k_pages):
 @pytest.mark.parametrize("max_pages,lens,per_thread", [
     (4096, (16 * 4096, 16 * 3000 + 1), 8),         # 512 threads x 8 keys
     (8192, (16 * 8192, 16 * 5000), 16),            # 512 x 16
+    (10000, (16 * 10000 - 5, 16 * 8193), 20),      # 512 x 20
     (12288, (16 * 12288 - 3, 16 * 9000), 12),      # 1024 x 12
     (32769, (16 * 32769, 16 * 20000 + 9), 33),     # 1024 x 33
     (65535, (16 * 65535, 16 * 40000), 64),         # 1024 x 64
