@@ -12,7 +12,8 @@
  *     every token   :  quest_append_meta -> quest_estimate -> quest_topk
  *                      -> quest_sparse_decode
  *                      (quest_append_estimate fuses the first two launches,
- *                       quest_decode_step all of them)
+ *                       quest_select_decode the last two; quest_decode_step
+ *                       is the whole step in one call)
  *
  * Conventions for every entry point
  *   - All data pointers are DEVICE pointers owned by the caller.  The library
@@ -30,7 +31,7 @@
  *     seq_lens are never used, whatever they contain).
  *   - Supported shapes: head_dim == 128; page_size 8, 16, 32 or 64 tokens (the
  *     paper's default is 16; Figure 8 sweeps the page size); multi-head
- *     attention (one KV head per query head).
+ *     attention (one KV head per query head) or grouped-query attention (below).
  *
  * Layouts (row-major, innermost last)
  *   k_pool, v_pool : fp16  [num_phys_pages][num_heads][page_size][head_dim]
