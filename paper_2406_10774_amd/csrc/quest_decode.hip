@@ -28,6 +28,7 @@
 
 #include <cmath>
 #include <cstdlib>
+#include <type_traits>
 
 namespace quest {
 
@@ -114,7 +115,8 @@ __global__ __launch_bounds__(kWaves* kWave) void decode_split_kernel(const Decod
   __shared__ float sm_acc[kDecWaves][kG][kHeadDim];
   __shared__ float sm_m[kDecWaves][kG], sm_l[kDecWaves][kG];
   __shared__ uint32_t sm_before[2];
-  __shared__ TopkShared<kWaves * kWave> sm_topk;
+  // the selection's LDS only where there is a selection
+  __shared__ typename std::conditional<(kSelItems > 0), TopkShared<kWaves * kWave>, char>::type sm_topk;
   __shared__ int32_t sm_list[kSelItems > 0 ? kSelListCap : 1];
 
   // blockIdx.x = slot + 8 * split, blockIdx.y = group of 8 items: the linear work-group
@@ -151,14 +153,14 @@ __global__ __launch_bounds__(kWaves* kWave) void decode_split_kernel(const Decod
   const int32_t* idx_row =
       a.topk_idx ? a.topk_idx + ((size_t)b * a.kv_heads + hk) * a.k_pages : nullptr;
   const int32_t* pt = a.page_table + (size_t)b * a.max_pages;
-  if (kSelItems > 0) {
+  if constexpr (kSelItems > 0) {
     const size_t row = (size_t)b * a.kv_heads + hk;
     const bool writer = split == 0 && h == hk * a.group;  // one work-group per list writes it out
     int32_t* out_row = a.topk_out + row * a.k_pages;
 #ifdef QUEST_STEP_TRACE
     if (threadIdx.x == 0) sm_topk.trace = a.trace ? a.trace + ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 16 : nullptr;
 #endif
-    topk_block_put<kWaves * kWave, (kSelItems > 0 ? kSelItems : 1)>(
+    topk_block_put<kWaves * kWave, kSelItems>(
         sm_topk, a.scores + row * a.max_pages, a.seq_lens + b, a.max_pages, a.k_pages,
         [&](int pos, int page) {
           sm_list[pos] = page;
