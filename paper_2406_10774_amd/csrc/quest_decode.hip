@@ -376,7 +376,7 @@ struct SplitPlan {
 };
 SplitPlan plan_splits(const quest_cache& c, int k_pages) {
   static const int pages_per_split = env_int("QUEST_DECODE_PAGES_PER_SPLIT", 16);
-  static const int max_groups = env_int("QUEST_DECODE_MAX_GROUPS", 1024);
+  static const int max_groups_env = env_int("QUEST_DECODE_MAX_GROUPS", 0);
   SplitPlan p;
   p.list_len = k_pages > 0 ? (k_pages < c.max_pages_per_seq ? k_pages : c.max_pages_per_seq)
                            : c.max_pages_per_seq;
@@ -394,6 +394,12 @@ SplitPlan plan_splits(const quest_cache& c, int k_pages) {
   const long finest = (p.list_len + unit - 1) / unit;
   if (splits < fill) splits = fill < finest ? fill : finest;
   const long qh = (long)c.batch * c.num_heads;  // a work-group's weight grows with its heads
+  // Work-groups in all: two per compute unit stream best once there is enough work
+  // (deeper streams per wave, fewer partial results to merge: 58 us against 62 us per
+  // step at 4 sequences of 32 heads, 104 against 109 at 8); a single sequence of 32 heads
+  // is faster with four (dense path: 100 us against 105 us).
+  const long max_groups = max_groups_env > 0 ? max_groups_env : qh <= 32 ? 4 * kComputeUnits
+                                                                        : 2 * kComputeUnits;
   const long cap = max_groups / qh > 0 ? max_groups / qh : 1;
   if (splits > cap) splits = cap;
   if (splits < 1) splits = 1;
