@@ -288,7 +288,7 @@ def main():
         cpu = cpu_baseline(w, table, k_pool, v_pool, lens0, scale)
 
     line = {
-        "metric": "sparse decode attn us/layer-step + achieved HBM GB/s (32 heads, 32k ctx, budget 2048)",
+        "metric": "sparse decode attn \u00b5s/layer-step + achieved HBM GB/s (32 heads, 32k ctx, budget 2048)",
         "value": round(us_step, 3), "unit": "us/layer-step",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(us_step * 1e-3, 6), "higher_is_better": False, "scaling": "weak",
