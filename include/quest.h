@@ -133,8 +133,9 @@ typedef struct quest_cache {
  * shape.  Calls that share a workspace must not overlap in time. */
 int quest_workspace_bytes(const quest_cache* cache, int32_t k_pages, size_t* out_bytes);
 
-/* Metadata of every page that holds at least one token (Section 3.4:
- * "maximum and minimum values of each feature dimension of the Key vector"):
+/* Metadata of every page that holds at least one token (Section 3.4): per
+ * head and channel, the smallest and the largest key value among the page's
+ * tokens:
  *   meta[h][phys][0][i] = min_j k[j][i],  meta[h][phys][1][i] = max_j k[j][i]
  * over the valid tokens j of the page (a partial last page: its first
  * seq_len - p*S slots).  Comparison is by value with -0 ordered below +0, so
@@ -174,17 +175,35 @@ int quest_append_estimate(const quest_cache* cache, const void* k_new, const voi
  * kept.  QUEST_FLAG_KEEP_* in cache->flags force pages into the list (see
  * there).  topk_idx[b][h][0..K_b) receives the chosen logical page ids in
  * ascending order, the rest of the row is set to -1.  k_eff (nullable, int32
- * [batch], device) receives K_b.  Deterministic. */
+ * [batch], device) receives K_b.  Deterministic.
+ * workspace (nullable): one work-group per row needs none, and that is what runs
+ * with workspace == NULL at any row length.  Rows of 16384 pages or more are
+ * selected faster in two stages (a work-group per 4096-page chunk keeps the
+ * chunk's best k_pages, a second launch selects among those candidates; same
+ * result bit for bit, ties and forced pages included) when a workspace of at
+ * least quest_topk_workspace_bytes(cache, k_pages) bytes is given; for shapes
+ * where that size is 0 the workspace is ignored. */
 int quest_topk(const quest_cache* cache, const float* scores, int32_t k_pages,
-               int32_t* topk_idx, int32_t* k_eff, void* stream);
+               int32_t* topk_idx, int32_t* k_eff, void* workspace, size_t workspace_bytes,
+               void* stream);
+
+/* Bytes of device workspace with which quest_topk selects in two stages (0: this
+ * shape is always selected by one work-group per row and needs none).  Pure host
+ * function.  The workspace holds the candidates of the first stage (score and page
+ * of the best k_pages of every 4096-page chunk of a row); it need not be
+ * initialised and keeps nothing between calls. */
+int quest_topk_workspace_bytes(const quest_cache* cache, int32_t k_pages, size_t* out_bytes);
 
 /* Approximate attention (Figure 5, stage 2): ordinary softmax attention of q
  * over the valid tokens of the listed pages only,
  *   out[b][h][:] = sum_j softmax_j(sm_scale * q.k_j) * v_j,
  *   lse[b][h]    = log sum_j exp(sm_scale * q.k_j)            (nullable).
- * topk_idx rows are read up to min(k_pages, P_b) entries and stop at the first
- * negative id.  topk_idx == NULL selects every page: the dense baseline
- * (k_pages is then ignored).  fp16 inputs, fp32 dot products, fp32 online
+ * The first min(k_pages, max_pages_per_seq) entries of a topk_idx row are
+ * read; an entry that is negative, or the id of a page without
+ * tokens (>= P_b), is skipped wherever it stands, so lists padded with -1 as
+ * quest_topk writes them need no length.  A page listed twice is attended
+ * twice.  topk_idx == NULL selects every page: the dense baseline (k_pages is
+ * then ignored).  fp16 inputs, fp32 dot products, fp32 online
  * softmax over splits of the page list; the split that finishes last merges
  * them.  out is fp32
  * if out_is_fp16 == 0, else fp16 (rounded once, from the fp32 result).

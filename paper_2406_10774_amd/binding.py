@@ -22,8 +22,9 @@ STATUS_NAMES = {0: "QUEST_OK", -1: "QUEST_ERR_NULL", -2: "QUEST_ERR_SHAPE",
                 -3: "QUEST_ERR_UNSUPPORTED", -4: "QUEST_ERR_WORKSPACE", -5: "QUEST_ERR_HIP"}
 
 EXPORTS = ("quest_workspace_bytes", "quest_build_meta", "quest_append_meta", "quest_estimate",
-           "quest_append_estimate", "quest_topk", "quest_sparse_decode", "quest_select_decode",
-           "quest_step_workspace_bytes", "quest_decode_step", "quest_last_error")
+           "quest_append_estimate", "quest_topk", "quest_topk_workspace_bytes", "quest_sparse_decode",
+           "quest_select_decode", "quest_step_workspace_bytes", "quest_decode_step",
+           "quest_last_error")
 
 
 class QuestError(RuntimeError):
@@ -64,7 +65,8 @@ def load():
     lib.quest_append_meta.argtypes = [cp, vp, vp, i32, vp]
     lib.quest_estimate.argtypes = [cp, vp, vp, vp]
     lib.quest_append_estimate.argtypes = [cp, vp, vp, i32, vp, vp, vp]
-    lib.quest_topk.argtypes = [cp, vp, i32, vp, vp, vp]
+    lib.quest_topk.argtypes = [cp, vp, i32, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.quest_topk_workspace_bytes.argtypes = [cp, i32, ctypes.POINTER(ctypes.c_size_t)]
     lib.quest_sparse_decode.argtypes = [cp, vp, vp, i32, f32, vp, i32, vp, vp, ctypes.c_size_t, vp]
     lib.quest_select_decode.argtypes = [cp, vp, vp, i32, f32, vp, vp, vp, i32, vp, vp, ctypes.c_size_t, vp]
     lib.quest_step_workspace_bytes.argtypes = [cp, i32, ctypes.POINTER(ctypes.c_size_t)]
@@ -143,9 +145,16 @@ def quest_append_estimate(cache: Cache, k_new, v_new, k_pool_write, q, scores, s
                                         _stream(stream)))
 
 
-def quest_topk(cache: Cache, scores, k_pages, topk_idx, k_eff=None, stream=None):
+def quest_topk(cache: Cache, scores, k_pages, topk_idx, k_eff=None, workspace=None, stream=None):
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load().quest_topk(cache.ref, _ptr(scores), int(k_pages), _ptr(topk_idx), _ptr(k_eff),
-                             _stream(stream)))
+                             _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def quest_topk_workspace_bytes(cache: Cache, k_pages: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().quest_topk_workspace_bytes(cache.ref, int(k_pages), ctypes.byref(out)))
+    return out.value
 
 
 def quest_sparse_decode(cache: Cache, q, topk_idx, k_pages, sm_scale, out, lse=None,
@@ -181,4 +190,5 @@ def quest_decode_step(cache: Cache, k_new, v_new, k_pool_write, q, k_pages, sm_s
         cache.ref, _ptr(k_new), _ptr(v_new), int(bool(k_pool_write)), _ptr(q), int(k_pages),
         float(sm_scale), _ptr(scores), _ptr(topk_idx), _ptr(k_eff), _ptr(out),
         int(out.dtype == torch.float16), _ptr(lse), _ptr(workspace), ws_bytes, _stream(stream)))
+
 

@@ -134,8 +134,19 @@ int quest_append_estimate(const quest_cache* cache, const void* k_new, const voi
                                 (hipStream_t)stream);
 }
 
+int quest_topk_workspace_bytes(const quest_cache* cache, int32_t k_pages, size_t* out_bytes) {
+  int r = check_cache(cache, "quest_topk_workspace_bytes");
+  if (r != QUEST_OK) return r;
+  if (out_bytes == nullptr) {
+    set_error("quest_topk_workspace_bytes: out_bytes is NULL");
+    return QUEST_ERR_NULL;
+  }
+  *out_bytes = k_pages >= 1 ? topk_scratch_bytes(*cache, k_pages) : 0;
+  return QUEST_OK;
+}
+
 int quest_topk(const quest_cache* cache, const float* scores, int32_t k_pages, int32_t* topk_idx,
-               int32_t* k_eff, void* stream) {
+               int32_t* k_eff, void* workspace, size_t workspace_bytes, void* stream) {
   int r = check_cache(cache, "quest_topk");
   if (r != QUEST_OK) return r;
   if (scores == nullptr || topk_idx == nullptr) {
@@ -146,7 +157,16 @@ int quest_topk(const quest_cache* cache, const float* scores, int32_t k_pages, i
     set_error("quest_topk: k_pages must be >= 1 (got %d)", k_pages);
     return QUEST_ERR_SHAPE;
   }
-  return launch_topk(*cache, scores, k_pages, topk_idx, k_eff, (hipStream_t)stream);
+  const size_t need = topk_scratch_bytes(*cache, k_pages);
+  if (workspace == nullptr || need == 0)  // one work-group per row
+    return launch_topk(*cache, scores, k_pages, topk_idx, k_eff, (hipStream_t)stream);
+  if (workspace_bytes < need) {
+    set_error("quest_topk: workspace of %zu bytes needed for the two-stage selection, %zu given "
+              "(pass NULL for the single-stage selection)", need, workspace_bytes);
+    return QUEST_ERR_WORKSPACE;
+  }
+  return launch_topk_chunked(*cache, scores, k_pages, topk_idx, k_eff, workspace,
+                             (hipStream_t)stream);
 }
 
 int quest_sparse_decode(const quest_cache* cache, const void* q, const int32_t* topk_idx,

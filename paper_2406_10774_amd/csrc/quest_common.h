@@ -65,6 +65,8 @@ int launch_select_decode(const quest_cache& c, const void* q, const float* score
                          int out_is_fp16, float* lse, void* workspace, hipStream_t s);
 
 size_t step_workspace_bytes(const quest_cache& c, int k_pages);
+// Leading part of a decode workspace: the arrival counters (must be zero before a launch).
+size_t decode_counter_bytes(const quest_cache& c);
 int launch_decode_step(const quest_cache& c, const void* k_new, const void* v_new, int k_pool_write,
                        const void* q, int k_pages, float sm_scale, float* scores, int32_t* topk_idx,
                        int32_t* k_eff, void* out, int out_is_fp16, float* lse, void* workspace,
@@ -78,6 +80,14 @@ __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 // 16-byte global load / store (global_load_dwordx4).
 __device__ __forceinline__ uint4 ld16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
 __device__ __forceinline__ void st16(void* p, uint4 v) { *reinterpret_cast<uint4*>(p) = v; }
+// The same load marked non-temporal, for data a launch touches once (metadata entries,
+// K/V pages): measured on MI355X, 32 MiB scanned in 6.1 us against 6.5 us, the dense
+// attention over 512 MiB in 88 us against 100 us.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 ld16_stream(const void* p) {
+  const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
 
 // x + (x rotated right by N lanes inside its 16-lane DPP row).
 template <int N>

@@ -27,7 +27,6 @@
 #include "quest_topk_core.h"
 
 #include <cmath>
-#include <cstdlib>
 #include <type_traits>
 
 namespace quest {
@@ -41,17 +40,6 @@ constexpr int kDecThreads = kDecWaves * kWave;
 // the selection is fastest at, and room in LDS for a page list of this many entries.
 constexpr int kSelWaves = 8;
 constexpr int kSelListCap = 2048;
-
-#ifdef QUEST_STEP_TRACE
-#define DEC_TRACE(slot)                                                                  \
-  do {                                                                                   \
-    if (threadIdx.x == 0 && a.trace) a.trace[((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 16 + (slot)] = wall_clock64(); \
-  } while (0)
-#else
-#define DEC_TRACE(slot) \
-  do {                  \
-  } while (0)
-#endif
 
 // The same value in a register that no load is outstanding for: the compiler waits for
 // `v` here, once, instead of before every later use it cannot order against other loads.
@@ -76,28 +64,22 @@ struct DecodeArgs {
   float* part_ml;           // [B*H*splits][2]   running max (log2 domain), denominator
   void* out;
   float* lse;
-  uint64_t* counters;       // [B*H] team words (see quest_team.h); zero between launches
+  uint64_t* counters;       // [B*H] arrival counters, one per 256-byte slot (quest_team.h); zero between launches
   int batch, num_heads, max_pages, k_pages, splits, out_is_fp16;
   int list_len;             // entries of the page list the splits divide: k_pages, or max_pages
   int per_split;            // ceil(list_len / splits)
-  int force_device_fences;  // debug: take the cross-die exchange path
+  int device_fences;        // QUEST_FLAG_DEVICE_FENCES: fences around the exchange as well
   int kv_heads, group;      // KV heads; query heads per KV head (num_heads = kv_heads * group)
   int page_shift;           // log2(tokens per page)
   int unit_shift;           // log2(streaming units per page): 0 up to 16 tokens, 1 for 32, 2 for 64
   float scale_log2;         // sm_scale * log2(e)
-#ifdef QUEST_STEP_TRACE
-  unsigned long long* trace;
-#endif
 };
 
-// The grid is die-aware: work-groups whose linear ids are equal modulo 8 run on the
-// same die (round-robin placement; grid.x is a multiple of 8), and
-// all splits of one (sequence, head) are given ids with the same i % 8, so
-// their partial results meet in one L2 and the last split to finish can merge
-// them without a second launch and without device-wide cache maintenance.
-// The placement is verified at run time (see quest_team.h): if the splits of a
-// head do not all run on one die, the exchange falls back to device-scope
-// release/acquire fences: slow, still correct.
+// All splits of one (sequence, head) get work-group ids that are equal modulo 8
+// (grid.x is a multiple of 8), so under the usual round-robin placement they run on
+// one die and their traffic stays in one L2.  Nothing depends on that: partial results
+// are handed over with device-scope stores and loads (quest_team.h), correct wherever
+// the splits run; the split that finishes last merges them, without a second launch.
 // kLoads: wave-wide 16-byte loads per unit of keys (and of values): 4, or 2 for 8-token
 // pages.  kG: query heads served by one work-group (they share the KV head, so a page is
 // loaded once for all of them): 1 unless grouped-query attention; a group of G heads is
@@ -114,10 +96,11 @@ __global__ __launch_bounds__(kWaves* kWave) void decode_split_kernel(const Decod
   constexpr int kDecWaves = kWaves;
   __shared__ float sm_acc[kDecWaves][kG][kHeadDim];
   __shared__ float sm_m[kDecWaves][kG], sm_l[kDecWaves][kG];
-  __shared__ uint32_t sm_before[2];
-  // the selection's LDS only where there is a selection
+  __shared__ uint32_t sm_before;
+  // the selection's LDS only where there is a selection; the list as (logical page,
+  // physical page) pairs
   __shared__ typename std::conditional<(kSelItems > 0), TopkShared<kWaves * kWave>, char>::type sm_topk;
-  __shared__ int32_t sm_list[kSelItems > 0 ? kSelListCap : 1];
+  __shared__ int2 sm_list[kSelItems > 0 ? kSelListCap : 1];
 
   // blockIdx.x = slot + 8 * split, blockIdx.y = group of 8 items: the linear work-group
   // id is slot + 8 * (split + splits * blockIdx.y).  The usual shapes (one sequence, one
@@ -138,10 +121,7 @@ __global__ __launch_bounds__(kWaves* kWave) void decode_split_kernel(const Decod
   const int lane = lane_id();
   const int grp = lane >> 4;
   const int c = lane & 15;
-  const uint32_t die = xcc_id();
-  DEC_TRACE(0);
-  uint64_t* team_word = a.counters + bh * kTeamWordStride;
-  if (a.splits > 1 && threadIdx.x == 0) team_checkin(team_word, die);
+  uint32_t* arrivals = reinterpret_cast<uint32_t*>(a.counters + bh * kTeamWordStride);
 
   // This wave's share of the page list: positions begin + wave + 4 i.  The list
   // length used for the split (k_pages, or max_pages without a list) is known
@@ -153,31 +133,51 @@ __global__ __launch_bounds__(kWaves* kWave) void decode_split_kernel(const Decod
   const int32_t* idx_row =
       a.topk_idx ? a.topk_idx + ((size_t)b * a.kv_heads + hk) * a.k_pages : nullptr;
   const int32_t* pt = a.page_table + (size_t)b * a.max_pages;
+  int seq_len;
+  uint4 qv[kG];
   if constexpr (kSelItems > 0) {
     const size_t row = (size_t)b * a.kv_heads + hk;
     const bool writer = split == 0 && h == hk * a.group;  // one work-group per list writes it out
     int32_t* out_row = a.topk_out + row * a.k_pages;
-#ifdef QUEST_STEP_TRACE
-    if (threadIdx.x == 0) sm_topk.trace = a.trace ? a.trace + ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 16 : nullptr;
-#endif
+    // Behind the loads of the scores (loads complete in order, so nothing may be in front
+    // of what the selection waits for): the page-table entries of this thread's pages,
+    // which travel with their scores so that the list needs no look-up afterwards, and
+    // what the attention needs besides the pages.
+    int my_phys[kSelItems];
+    auto more_loads = [&] {
+#pragma unroll
+      for (int j = 0; j < kSelItems; ++j)
+        my_phys[j] = pt[min((int)threadIdx.x * kSelItems + j, a.max_pages - 1)];
+      seq_len = a.seq_lens[b];
+#pragma unroll
+      for (int g = 0; g < kG; ++g) qv[g] = ld16(a.q + (bh + g) * (kHeadDim * 2) + c * 16);
+    };
     topk_block_put<kWaves * kWave, kSelItems>(
         sm_topk, a.scores + row * a.max_pages, a.seq_lens + b, a.max_pages, a.k_pages,
-        [&](int pos, int page) {
-          sm_list[pos] = page;
+        [&](int pos, int page, int j) {
+          int phys = 0;
+          if (j >= 0) {
+#pragma unroll
+            for (int jj = 0; jj < kSelItems; ++jj)
+              if (jj == j) phys = my_phys[jj];
+          } else if (page >= 0) {
+            phys = pt[page];
+          }
+          sm_list[pos] = make_int2(page, phys);
           if (writer) out_row[pos] = page;
         },
         (writer && hk == 0 && a.k_eff != nullptr) ? a.k_eff + b : nullptr,
-        WholeRow{a.page_shift, a.policy});
+        WholeRow{a.page_shift, a.policy}, more_loads);
     __syncthreads();
-    DEC_TRACE(6);
+  } else {
+    seq_len = a.seq_lens[b];
+#pragma unroll
+    for (int g = 0; g < kG; ++g) qv[g] = ld16(a.q + (bh + g) * (kHeadDim * 2) + c * 16);
   }
 
-  const int seq_len = a.seq_lens[b];
-  uint4 qv[kG];
   Softmax st[kG];
 #pragma unroll
   for (int g = 0; g < kG; ++g) {
-    qv[g] = ld16(a.q + (bh + g) * (kHeadDim * 2) + c * 16);
     st[g].m = kNegBig;
     st[g].l = 0.f;
 #pragma unroll
@@ -193,16 +193,21 @@ __global__ __launch_bounds__(kWaves* kWave) void decode_split_kernel(const Decod
     const int e = u >> a.unit_shift;
     const int un_v = u & ((1 << a.unit_shift) - 1);
     const int pos = begin + wave + kDecWaves * e;
-    int lp_v = -1;
-    if (e < iters && pos < end) lp_v = kSelItems > 0 ? sm_list[pos] : idx_row ? idx_row[pos] : pos;
-    int ph_v = 0;
-    if (lp_v >= 0 && lp_v < a.max_pages) ph_v = pt[lp_v];
+    int lp_v = -1, ph_v = 0;
+    if constexpr (kSelItems > 0) {
+      if (e < iters && pos < end) {
+        const int2 entry = sm_list[pos];
+        lp_v = entry.x, ph_v = entry.y;
+      }
+    } else {
+      if (e < iters && pos < end) lp_v = idx_row ? idx_row[pos] : pos;
+      if (lp_v >= 0 && lp_v < a.max_pages) ph_v = pt[lp_v];
+    }
     if (lp_v >= num_pages) lp_v = -1;
-    if (__builtin_amdgcn_readlane(ph_v, 0) >= 0) DEC_TRACE(1);
 
 #define QUEST_LOAD_UNIT(regs, i)                                                               \
   load_unit<kLoads>(regs, a.k_pool, a.v_pool, a.kv_heads, hk, seq_len, __builtin_amdgcn_readlane(lp_v, i), \
-                    __builtin_amdgcn_readlane(ph_v, i), __builtin_amdgcn_readlane(un_v, i),    \
+                    __builtin_amdgcn_readlane(ph_v, i), __builtin_amdgcn_readlane(un_c, i),    \
                     a.page_shift, lane)
 #define QUEST_FOLD(regs)                                  \
   do {                                                    \
@@ -211,15 +216,27 @@ __global__ __launch_bounds__(kWaves* kWave) void decode_split_kernel(const Decod
     else                                                  \
       fold_group(st, regs, qv, a.scale_log2, grp);        \
   } while (0)
-    // The valid units of a round are its first n lanes (lists are ascending and padded
-    // at the end).  Two units in flight per wave: the next one is requested before the
-    // current one is folded.  Every load inside the loop is unconditional and the index
-    // registers are detached from the loads that produced them (one wait here), so the
-    // compiler's wait counts inside the loop are exact: a conditional load, or an index
-    // still marked as in flight, makes it wait for everything outstanding at every
-    // step, which leaves a single unit in flight.
+    // The units to stream are moved to the first n lanes (lists from the selection are
+    // ascending and padded at the end, so normally they are there already; a caller's
+    // list may have negative or out-of-range entries anywhere: those are skipped).
+    // Two units in flight per wave: the next one is requested before the current one is
+    // folded.  Every load inside the loop is unconditional and the index registers are
+    // detached from the loads that produced them (one wait here), so the compiler's
+    // wait counts inside the loop are exact: a conditional load, or an index still
+    // marked as in flight, makes it wait for everything outstanding at every step,
+    // which leaves a single unit in flight.
     const unsigned long long live = __ballot(lp_v >= 0);
-    const int n = live == ~0ull ? kWave : __ffsll((long long)~live) - 1;
+    const int n = __popcll(live);
+    int un_c = un_v;
+    if (live & (live + 1)) {  // not a prefix of the lanes: compact (wave-uniform branch)
+      const int to = lp_v >= 0 ? (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(live >> 32),
+                                      __builtin_amdgcn_mbcnt_lo((uint32_t)live, 0u)) : kWave - 1;
+      // a dead lane's target is lane 63, which no live lane can have unless all 64 are
+      // live (then this branch is not taken); its value there is never used (63 >= n)
+      lp_v = __builtin_amdgcn_ds_permute(to * 4, lp_v);
+      ph_v = __builtin_amdgcn_ds_permute(to * 4, ph_v);
+      un_c = __builtin_amdgcn_ds_permute(to * 4, un_v);
+    }
     lp_v = settled(lp_v);
     ph_v = settled(ph_v);
     PageRegsT<kLoads> ra, rb;
@@ -245,11 +262,6 @@ __global__ __launch_bounds__(kWaves* kWave) void decode_split_kernel(const Decod
   }
 
   // the four DPP rows of the wave, then the four waves of the group
-  DEC_TRACE(2);
-  // every member checked in when it started, microseconds ago: read the team word
-  // now, the answer is needed only when this split publishes
-  uint64_t seen = 0;
-  if (a.splits > 1 && threadIdx.x == 0) seen = team_load(team_word);
 #pragma unroll
   for (int g = 0; g < kG; ++g) {
     merge_lanes(st[g], 16);
@@ -266,7 +278,7 @@ __global__ __launch_bounds__(kWaves* kWave) void decode_split_kernel(const Decod
   __syncthreads();
   const int t = threadIdx.x;
   // ---- this split's result per query head: written out if it is the only split, else
-  // published as a partial; the split that finishes last merges
+  // published as a partial; the split that arrives last merges
 #pragma unroll
   for (int g = 0; g < kG; ++g) {
     float m_tot = sm_m[0][g];
@@ -286,56 +298,50 @@ __global__ __launch_bounds__(kWaves* kWave) void decode_split_kernel(const Decod
       }
     } else {
       const size_t ps = (bh + g) * a.splits + split;
-      if (t < kHeadDim) a.part_acc[ps * kHeadDim + t] = acc;
+      if (t < kHeadDim) dev_st(a.part_acc + ps * kHeadDim + t, acc);
       if (t == 0) {
-        a.part_ml[ps * 2 + 0] = m_tot;
-        a.part_ml[ps * 2 + 1] = l_tot;
+        dev_st(a.part_ml + ps * 2 + 0, m_tot);
+        dev_st(a.part_ml + ps * 2 + 1, l_tot);
       }
     }
   }
   if (a.splits == 1) return;
-  DEC_TRACE(3);
   wait_stores();
   __syncthreads();
-  if (t == 0) {
-    const uint64_t before = team_publish(team_word, seen, a.splits, die, a.force_device_fences);
-    sm_before[0] = (uint32_t)before;
-    sm_before[1] = (uint32_t)(before >> 32);
-  }
+  if (t == 0) sm_before = team_arrive(arrivals, a.device_fences);
   __syncthreads();
-  const uint64_t before = sm_before[0] | ((uint64_t)sm_before[1] << 32);
-  DEC_TRACE(4);
-  if (!team_is_last(before, a.splits)) return;
-  team_acquire(before, a.splits, die, a.force_device_fences);
-  if (t == 0) team_reset(team_word);
+  if (__builtin_amdgcn_readfirstlane(sm_before) != (uint32_t)a.splits - 1) return;
+  team_acquire(a.device_fences);
+  if (t == 0) team_reset(arrivals);
 
-  // one pass over the splits in chunks of 16, all loads of a chunk in flight at
-  // once, with a running maximum (the same rescaling as between pages)
+  // one pass over the splits in chunks of 8, all loads of a chunk in flight at once, with
+  // a running maximum (the same rescaling as between pages); always in split order, so the
+  // result does not depend on which split arrived last
   if (t >= kHeadDim) return;
 #pragma unroll 1
   for (int g = 0; g < kG; ++g) {
     const float* ml = a.part_ml + (bh + g) * a.splits * 2;
     const float* pacc = a.part_acc + (bh + g) * a.splits * kHeadDim + t;
     float mx = kNegBig, l_all = 0.f, o = 0.f;
-    for (int s0 = 0; s0 < a.splits; s0 += 16) {
-      float pm[16], pl[16], pa[16];
+    for (int s0 = 0; s0 < a.splits; s0 += 8) {
+      float2 pml[8];
+      float pa[8];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
+      for (int i = 0; i < 8; ++i) {
         const int sidx = min(s0 + i, a.splits - 1);
-        pm[i] = team_ld(ml + 2 * sidx);
-        pl[i] = team_ld(ml + 2 * sidx + 1);
-        pa[i] = team_ld(pacc + (size_t)sidx * kHeadDim);
+        pml[i] = dev_ld2(ml + 2 * sidx);
+        pa[i] = dev_ld(pacc + (size_t)sidx * kHeadDim);
       }
       float cm = mx;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) cm = fmaxf(cm, pm[i]);
+      for (int i = 0; i < 8; ++i) cm = fmaxf(cm, pml[i].x);
       const float rescale = __builtin_amdgcn_exp2f(mx - cm);
       l_all *= rescale;
       o *= rescale;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const float f = s0 + i < a.splits ? __builtin_amdgcn_exp2f(pm[i] - cm) : 0.f;
-        l_all += pl[i] * f;
+      for (int i = 0; i < 8; ++i) {
+        const float f = s0 + i < a.splits ? __builtin_amdgcn_exp2f(pml[i].x - cm) : 0.f;
+        l_all += pml[i].y * f;
         o += pa[i] * f;
       }
       mx = cm;
@@ -343,12 +349,6 @@ __global__ __launch_bounds__(kWaves* kWave) void decode_split_kernel(const Decod
     store_out(a.out, a.out_is_fp16, (bh + g) * kHeadDim + t, o / l_all);
     if (t == 0 && a.lse) a.lse[bh + g] = (mx + __builtin_amdgcn_logf(l_all)) * kLn2;
   }
-  DEC_TRACE(5);
-}
-
-int env_int(const char* name, int fallback) {
-  const char* v = std::getenv(name);
-  return (v && *v) ? std::atoi(v) : fallback;
 }
 
 }  // namespace
@@ -356,9 +356,7 @@ int env_int(const char* name, int fallback) {
 // Number of splits of a head's page list.  A split holds at least 256 tokens (sixteen
 // pages of 16: four per wave, two in flight at a time), and the whole launch stays within
 // the ~1000 work-groups that are resident at once, so that all splits of a head
-// start together (the condition for the cheap same-die exchange) and the
-// merge reads few partial results.  Both knobs can be overridden through the
-// environment for tuning sweeps.
+// start together and the merge reads few partial results.
 namespace {
 // Query heads one work-group serves.  Heads of a group share a KV head, so its pages can
 // be loaded once for several of them: that pays on the dense path (4x less traffic; 47 us
@@ -375,8 +373,7 @@ struct SplitPlan {
   int list_len, per_split, splits;
 };
 SplitPlan plan_splits(const quest_cache& c, int k_pages) {
-  static const int pages_per_split = env_int("QUEST_DECODE_PAGES_PER_SPLIT", 16);
-  static const int max_groups_env = env_int("QUEST_DECODE_MAX_GROUPS", 0);
+  constexpr int pages_per_split = 16;
   SplitPlan p;
   p.list_len = k_pages > 0 ? (k_pages < c.max_pages_per_seq ? k_pages : c.max_pages_per_seq)
                            : c.max_pages_per_seq;
@@ -398,8 +395,7 @@ SplitPlan plan_splits(const quest_cache& c, int k_pages) {
   // (deeper streams per wave, fewer partial results to merge: 58 us against 62 us per
   // step at 4 sequences of 32 heads, 104 against 109 at 8); a single sequence of 32 heads
   // is faster with four (dense path: 100 us against 105 us).
-  const long max_groups = max_groups_env > 0 ? max_groups_env : qh <= 32 ? 4 * kComputeUnits
-                                                                        : 2 * kComputeUnits;
+  const long max_groups = qh <= 32 ? 4 * kComputeUnits : 2 * kComputeUnits;
   const long cap = max_groups / qh > 0 ? max_groups / qh : 1;
   if (splits > cap) splits = cap;
   if (splits < 1) splits = 1;
@@ -408,11 +404,13 @@ SplitPlan plan_splits(const quest_cache& c, int k_pages) {
   p.splits = (p.list_len + p.per_split - 1) / p.per_split;  // no empty split
   return p;
 }
-// One team word per (sequence, head), each in a 256-byte slot of its own.
+// One arrival counter per (sequence, head), each in a 256-byte slot of its own.
 size_t counter_bytes(const quest_cache& c) {
   return (size_t)c.batch * c.num_heads * kTeamWordStride * sizeof(uint64_t);
 }
 }  // namespace
+
+size_t decode_counter_bytes(const quest_cache& c) { return counter_bytes(c); }
 
 int decode_num_splits(const quest_cache& c, int k_pages) { return plan_splits(c, k_pages).splits; }
 
@@ -428,7 +426,6 @@ namespace {
 int launch_decode(const quest_cache& c, const void* q, const int32_t* topk_idx, const float* scores,
                   int32_t* topk_out, int32_t* k_eff, int k_pages, float sm_scale, void* out,
                   int out_is_fp16, float* lse, void* workspace, hipStream_t s) {
-  static const int force_fences = env_int("QUEST_FORCE_DEVICE_FENCES", 0);
   const bool select = scores != nullptr;
   DecodeArgs a;
   a.k_pool = (const char*)c.k_pool;
@@ -451,18 +448,13 @@ int launch_decode(const quest_cache& c, const void* q, const int32_t* topk_idx, 
   a.splits = p.splits;
   a.list_len = p.list_len;
   a.per_split = p.per_split;
-  a.force_device_fences = force_fences || (c.flags & QUEST_FLAG_DEVICE_FENCES) != 0;
+  a.device_fences = (c.flags & QUEST_FLAG_DEVICE_FENCES) != 0;
   a.out = out;
   a.out_is_fp16 = out_is_fp16;
   a.lse = lse;
   a.scale_log2 = sm_scale * kLog2e;
   a.page_shift = page_shift_of(c.page_size);
   a.unit_shift = a.page_shift > 4 ? a.page_shift - 4 : 0;
-#ifdef QUEST_STEP_TRACE
-  a.trace = std::getenv("QUEST_STEP_TRACE_PTR")
-                ? (unsigned long long*)std::strtoull(std::getenv("QUEST_STEP_TRACE_PTR"), nullptr, 16)
-                : nullptr;
-#endif
   const size_t n_part = (size_t)c.batch * c.num_heads * a.splits;
   a.counters = (uint64_t*)workspace;
   a.part_acc = workspace ? (float*)((char*)workspace + counter_bytes(c)) : nullptr;
@@ -520,8 +512,7 @@ int launch_sparse_decode(const quest_cache& c, const void* q, const int32_t* top
 // split of a head repeats the selection, so for longer rows (measured at 4097 pages:
 // 34.9 us against 34.2 us) the separate Top-K launch is the faster form.
 bool select_decode_supported(const quest_cache& c, int k_pages) {
-  static const int off = env_int("QUEST_NO_SELECT_DECODE", 0);
-  return !off && !(c.flags & QUEST_FLAG_SEPARATE_LAUNCHES) &&
+  return !(c.flags & QUEST_FLAG_SEPARATE_LAUNCHES) &&
          c.max_pages_per_seq <= kSelWaves * kWave * 8 && k_pages <= kSelListCap;
 }
 

@@ -43,9 +43,9 @@ __device__ __forceinline__ void load_unit(PageRegsT<kLoads>& r, const char* __re
   const size_t row = (((size_t)phys * num_heads + h) << page_shift) + (size_t)unit * (4 * kLoads);
   const size_t off = row * kRowBytes + lane * 16;
 #pragma unroll
-  for (int i = 0; i < kLoads; ++i) r.k[i] = ld16(k_pool + off + i * 1024);
+  for (int i = 0; i < kLoads; ++i) r.k[i] = ld16_stream(k_pool + off + i * 1024);
 #pragma unroll
-  for (int i = 0; i < kLoads; ++i) r.v[i] = ld16(v_pool + off + i * 1024);
+  for (int i = 0; i < kLoads; ++i) r.v[i] = ld16_stream(v_pool + off + i * 1024);
   r.n_valid = min(4 * kLoads, seq_len - (logical_page << page_shift) - unit * (4 * kLoads));
 }
 

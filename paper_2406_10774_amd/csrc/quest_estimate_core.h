@@ -8,7 +8,7 @@ namespace quest {
 
 #if defined(__HIPCC__)
 
-constexpr int kEstIters = 4;                     // wave-wide load pairs per wave (stand-alone kernel)
+constexpr int kEstIters = 4;                     // wave-wide load pairs per wave (large tables)
 constexpr int kEstPagesPerWave = 4 * kEstIters;  // 16
 
 // kAppend: the wave that owns the newest token's page first performs the
@@ -76,8 +76,8 @@ __device__ __forceinline__ void estimate_wave(const EstimateArgs& a, int b, int 
     mx[it] = make_uint4(0, 0, 0, 0);
     if (p < num_pages) {
       const char* entry = meta + meta_offset(a.num_phys_pages, phys[it], h) + c * 16;
-      mn[it] = ld16(entry);
-      mx[it] = ld16(entry + kHeadDim * 2);
+      mn[it] = ld16_stream(entry);
+      mx[it] = ld16_stream(entry + kHeadDim * 2);
     }
   }
 

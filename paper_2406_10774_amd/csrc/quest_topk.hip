@@ -1,5 +1,6 @@
-// Top-K page selection (Section 3.4 of arXiv 2406.10774: "choose the top K
-// pages as critical").  One work-group per (sequence, head).
+// Top-K page selection (Section 3.4 of arXiv 2406.10774: the K pages with the
+// largest criticality score are the ones attended).  One work-group per
+// (sequence, head).
 //
 // Scores are mapped to unsigned 32-bit keys whose integer order equals the
 // order of the float values (-0 folded onto +0), taken relative to the row's
@@ -35,9 +36,6 @@ __global__ __launch_bounds__(kThreads) void topk_kernel(
     int32_t* __restrict__ topk_idx, int32_t* __restrict__ k_eff, int num_heads, int max_pages,
     int k_pages, int page_shift, int policy) {
   __shared__ TopkShared<kThreads> sm;
-#ifdef QUEST_STEP_TRACE
-  if (threadIdx.x == 0) sm.trace = nullptr;
-#endif
   const int h = blockIdx.x;
   const int b = blockIdx.y;
   const size_t bh = (size_t)b * num_heads + h;
@@ -164,9 +162,6 @@ __global__ __launch_bounds__(kChunkThreads) void topk_chunk_kernel(
     float* __restrict__ cand_score, int32_t* __restrict__ cand_page, int num_heads, int max_pages,
     int k_pages, int num_chunks, int page_shift, int policy) {
   __shared__ TopkShared<kChunkThreads> sm;
-#ifdef QUEST_STEP_TRACE
-  if (threadIdx.x == 0) sm.trace = nullptr;
-#endif
   const int chunk = blockIdx.x;
   const int h = blockIdx.y;
   const int b = blockIdx.z;
@@ -177,13 +172,13 @@ __global__ __launch_bounds__(kChunkThreads) void topk_chunk_kernel(
   int32_t* out_page = cand_page + at;
   topk_block_put<kChunkThreads, kChunkItems>(
       sm, row, seq_lens + b, min(kChunkPages, max_pages - chunk * kChunkPages), k_pages,
-      [=](int pos, int page) {
+      [=](int pos, int page, int) {
         if (page >= 0) {
           out_page[pos] = page + chunk * kChunkPages;
           out_score[pos] = row[page];
         }
       },
-      nullptr, ChunkOfRow{page_shift, policy, chunk});
+      nullptr, ChunkOfRow{page_shift, policy, chunk}, [] {});
 }
 
 struct CandidateRow {
@@ -202,9 +197,6 @@ __global__ __launch_bounds__(kThreads) void topk_candidates_kernel(
     int32_t* __restrict__ k_eff, int num_heads, int row_len, int k_pages, int page_shift,
     int policy) {
   __shared__ TopkShared<kThreads> sm;
-#ifdef QUEST_STEP_TRACE
-  if (threadIdx.x == 0) sm.trace = nullptr;
-#endif
   const int h = blockIdx.x;
   const int b = blockIdx.y;
   const size_t bh = (size_t)b * num_heads + h;
@@ -212,8 +204,9 @@ __global__ __launch_bounds__(kThreads) void topk_candidates_kernel(
   int32_t* out = topk_idx + bh * k_pages;
   topk_block_put<kThreads, kItems>(
       sm, cand_score + bh * row_len, seq_lens + b, row_len, k_pages,
-      [=](int pos, int cand) { out[pos] = cand >= 0 ? pages[cand] : -1; },
-      (h == 0 && k_eff != nullptr) ? k_eff + b : nullptr, CandidateRow{page_shift, policy, k_pages});
+      [=](int pos, int cand, int) { out[pos] = cand >= 0 ? pages[cand] : -1; },
+      (h == 0 && k_eff != nullptr) ? k_eff + b : nullptr, CandidateRow{page_shift, policy, k_pages},
+      [] {});
 }
 
 template <int kThreads, int kItems>

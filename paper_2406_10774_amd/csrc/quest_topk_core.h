@@ -107,21 +107,7 @@ struct TopkShared {
   uint32_t hist[kMaxHistCopies0 + 3][256];  // copies for the first digit, then one per later digit
   int wave_tot[kThreads / kWave];
   uint32_t range[kThreads / kWave][2];  // smallest and largest key seen by each wave
-#ifdef QUEST_STEP_TRACE
-  unsigned long long* trace;  // set by the caller: time stamps of the phases, or nullptr
-#endif
 };
-
-#ifdef QUEST_STEP_TRACE
-#define TOPK_TRACE(slot)                                                           \
-  do {                                                                             \
-    if (threadIdx.x == 0 && sm.trace) sm.trace[(slot)] = wall_clock64();           \
-  } while (0)
-#else
-#define TOPK_TRACE(slot) \
-  do {                   \
-  } while (0)
-#endif
 
 // What a row of scores is, given the sequence length: its number of valid entries and
 // which of them are kept whatever their score (QUEST_FLAG_KEEP_* bits).
@@ -138,14 +124,18 @@ struct WholeRow {
 
 // Selection for one row of scores by one work-group of kThreads threads (all of
 // them must call).  shape(seq_len) describes the row (it has room for max_pages
-// entries); put(position, page) receives the list: positions 0 .. k_pages-1, pages
-// ascending, -1 past the K_b selected ones.
-template <int kThreads, int kItems, class Put, class Shape>
+// entries); put(position, page, j) receives the list: positions 0 .. k_pages-1, pages
+// ascending, -1 past the K_b selected ones; j >= 0 says that the page is the calling
+// thread's j-th one (page == threadIdx.x * kItems + j), j < 0 that it is not.
+// after_loads() is called once, right after the loads of the scores have been issued:
+// the place for loads the caller wants in flight behind them.
+template <int kThreads, int kItems, class Put, class Shape, class AfterLoads>
 __device__ __forceinline__ void topk_block_put(TopkShared<kThreads>& sm,
                                                const float* __restrict__ row,
                                                const int32_t* __restrict__ seq_len_ptr,
                                                int max_pages, int k_pages, Put put,
-                                               int32_t* __restrict__ k_eff_slot, Shape shape) {
+                                               int32_t* __restrict__ k_eff_slot, Shape shape,
+                                               AfterLoads after_loads) {
   constexpr int kWaves = kThreads / kWave;
   constexpr int kCopies0 = hist_copies0(kItems);
   uint32_t(&hist)[kMaxHistCopies0 + 3][256] = sm.hist;
@@ -167,6 +157,7 @@ __device__ __forceinline__ void topk_block_put(TopkShared<kThreads>& sm,
     raw[j] = row[i];
   }
   const int seq_len = *seq_len_ptr;
+  after_loads();
 
   for (int i = tid; i < (kCopies0 + 3) * 256; i += kThreads) (&hist[0][0])[i] = 0;
 
@@ -175,7 +166,7 @@ __device__ __forceinline__ void topk_block_put(TopkShared<kThreads>& sm,
   const int K = min(k_pages, num_pages);
   if (tid == 0 && k_eff_slot != nullptr) *k_eff_slot = K;
   if (K == num_pages) {  // everything is selected: identity list, padded with -1
-    for (int i = tid; i < k_pages; i += kThreads) put(i, i < K ? i : -1);
+    for (int i = tid; i < k_pages; i += kThreads) put(i, i < K ? i : -1, -1);
     return;
   }
 
@@ -185,8 +176,8 @@ __device__ __forceinline__ void topk_block_put(TopkShared<kThreads>& sm,
   const ForcedPages forced = forced_pages(row_shape.policy, num_pages);
   if (forced.count >= K) {  // K is 1 or 2 here: the list is the forced pages, lowest first
     if (tid == 0) {
-      put(0, forced.first ? 0 : num_pages - 1);
-      if (K == 2) put(1, num_pages - 1);
+      put(0, forced.first ? 0 : num_pages - 1, -1);
+      if (K == 2) put(1, num_pages - 1, -1);
     }
     return;
   }
@@ -205,13 +196,11 @@ __device__ __forceinline__ void topk_block_put(TopkShared<kThreads>& sm,
   lo = wave_min(lo);
   hi = wave_max(hi);
   if (lane == 0) range[wave][0] = lo, range[wave][1] = hi;
-  TOPK_TRACE(7);  // scores there
   __syncthreads();
 #pragma unroll
   for (int w = 0; w < kWaves; ++w) lo = min(lo, range[w][0]), hi = max(hi, range[w][1]);
   lo = __builtin_amdgcn_readfirstlane(lo);
   hi = __builtin_amdgcn_readfirstlane(hi);
-  TOPK_TRACE(12);
 
   // ---- radix select on (key - lo), shifted left so that the range's leading bit is
   // bit 31: the first digit already spreads the row over the histogram, and only
@@ -249,15 +238,12 @@ __device__ __forceinline__ void topk_block_put(TopkShared<kThreads>& sm,
         atomicAdd(&hp[digit], 1u);
       }
     }
-    if (pass == 0) TOPK_TRACE(13);
     __syncthreads();
-    if (pass == 0) TOPK_TRACE(14);
     const BinHit hit = pass == 0 ? find_bin<kCopies0>(hist[0], need, lane)
                                  : find_bin(hp, need, lane);
     prefix |= (uint32_t)hit.bin << shift;
     need -= hit.above;
     decided_shift = shift;
-    TOPK_TRACE(8 + pass);
     if (need == hit.count) break;  // the whole bin is selected: no need to split it further
   }
 
@@ -284,7 +270,7 @@ __device__ __forceinline__ void topk_block_put(TopkShared<kThreads>& sm,
 #pragma unroll
   for (int j = 0; j < kItems; ++j) {
     const bool sel = gt[j] || (eq[j] && eq_before < need);
-    if (sel) put(gt_before + min(eq_before, need), base + j);
+    if (sel) put(gt_before + min(eq_before, need), base + j, j);
     gt_before += gt[j];
     eq_before += eq[j];
   }
@@ -298,8 +284,8 @@ __device__ __forceinline__ void topk_block(TopkShared<kThreads>& sm, const float
                                            int32_t* __restrict__ k_eff_slot, int page_shift,
                                            int policy) {
   topk_block_put<kThreads, kItems>(
-      sm, row, seq_len_ptr, max_pages, k_pages, [out](int pos, int page) { out[pos] = page; },
-      k_eff_slot, WholeRow{page_shift, policy});
+      sm, row, seq_len_ptr, max_pages, k_pages, [out](int pos, int page, int) { out[pos] = page; },
+      k_eff_slot, WholeRow{page_shift, policy}, [] {});
 }
 
 #endif  // __HIPCC__

@@ -69,8 +69,8 @@ def test_null_and_range_arguments():
     assert lib.quest_estimate(r, 0x1000, None, None) == -1
     assert lib.quest_append_meta(r, None, None, 0, None) == -1
     assert lib.quest_append_meta(r, 0x1000, None, 1, None) == -1     # pool write needs v_new
-    assert lib.quest_topk(r, 0x1000, 0, 0x1000, None, None) == -2    # k_pages < 1
-    assert lib.quest_topk(r, None, 4, 0x1000, None, None) == -1
+    assert lib.quest_topk(r, 0x1000, 0, 0x1000, None, None, 0, None) == -2    # k_pages < 1
+    assert lib.quest_topk(r, None, 4, 0x1000, None, None, 0, None) == -1
     assert lib.quest_sparse_decode(r, 0x1000, 0x1000, 0, 1.0, 0x1000, 0, None, 0x1000, 1 << 30,
                                    None) == -2
     # workspace too small / missing

@@ -166,12 +166,25 @@ def test_topk_long_rows(max_pages, lens, per_thread):
     cache = Q.Cache(dummy, dummy, meta, pt, torch.from_numpy(lens).to(dev))
     scd = torch.from_numpy(sc).to(dev)
     for k_pages in (1, 256, 4097):
-        idx = torch.full((B, H, k_pages), -7, dtype=torch.int32, device=dev)
-        keff = torch.full((B,), -7, dtype=torch.int32, device=dev)
-        Q.quest_topk(cache, scd, k_pages, idx, keff)
         want, want_keff = O.topk(sc, lens, S, k_pages)
-        assert np.array_equal(keff.cpu().numpy(), want_keff)
-        assert np.array_equal(idx.cpu().numpy(), want), (max_pages, k_pages)
+        # without a workspace: one work-group per row; with one: two stages where the
+        # library offers them (rows from 16384 pages on, few enough candidates)
+        ws_bytes = Q.quest_topk_workspace_bytes(cache, k_pages)
+        assert (ws_bytes > 0) == (max_pages >= 16384 and k_pages <= 4096), (max_pages, k_pages)
+        for with_ws in (False, True):
+            if with_ws and ws_bytes == 0:
+                continue
+            ws = torch.empty(ws_bytes // 4, dtype=torch.int32, device=dev).fill_(-1) if with_ws else None
+            idx = torch.full((B, H, k_pages), -7, dtype=torch.int32, device=dev)
+            keff = torch.full((B,), -7, dtype=torch.int32, device=dev)
+            Q.quest_topk(cache, scd, k_pages, idx, keff, workspace=ws)
+            assert np.array_equal(keff.cpu().numpy(), want_keff)
+            assert np.array_equal(idx.cpu().numpy(), want), (max_pages, k_pages, with_ws)
+    if max_pages >= 16384:                             # a workspace that is too small is refused
+        small = torch.zeros(4, dtype=torch.int32, device=dev)
+        with pytest.raises(Q.QuestError) as err:
+            Q.quest_topk(cache, scd, 256, idx, None, workspace=small)
+        assert err.value.status == -4
 
 
 @pytest.mark.parametrize("policy", [0, 12])
@@ -320,6 +333,35 @@ def test_sparse_decode_against_oracle(ragged):
     w16 = want.astype(np.float16)
     ulp = np.maximum(np.abs(np.spacing(w16)).astype(np.float64), 2.0 ** -24)
     assert (np.abs(got16.astype(np.float64) - w16.astype(np.float64)) <= ulp).all()
+
+
+def test_sparse_decode_skips_invalid_list_entries(ragged):
+    """A caller's page list may hold negative ids and ids of pages without tokens anywhere,
+    not only as padding at the end: every such entry is skipped, the others are attended."""
+    w, table, N, k_pool, v_pool, q, lens, layer = ragged
+    meta = O.build_meta(k_pool, table, lens)
+    sc = O.estimate(meta, q, table, lens, w.page_size)
+    scale = 1 / math.sqrt(w.head_dim)
+    rng = np.random.default_rng(5)
+    for k_pages in (5, 24, 100):
+        idx, _ = O.topk(sc, lens, w.page_size, k_pages)
+        holes = idx.copy()
+        for b in range(w.batch):
+            K = min(k_pages, w.pages_of(b))
+            for h in range(w.num_heads):
+                if K < 2:
+                    continue
+                drop = rng.choice(K, size=max(1, K // 3), replace=False)
+                drop = drop[drop != int(rng.integers(K))][:K - 1]     # keep at least one entry
+                kinds = rng.integers(0, 3, size=len(drop))
+                holes[b, h, drop] = np.where(kinds == 0, -1, np.where(kinds == 1, -12345,
+                                                                      w.pages_of(b) + kinds))
+        cleaned = np.where((holes >= 0) & (holes < np.array([w.pages_of(b) for b in range(w.batch)])
+                                           [:, None, None]), holes, -1)
+        want, want_lse = O.sparse_decode(k_pool, v_pool, q, table, lens, cleaned, scale)
+        got, lse = layer.decode(q, holes, k_pages)
+        assert np.abs(got - want).max() <= ATTN_TOL, k_pages
+        assert np.abs(lse - want_lse).max() <= ATTN_TOL
 
 
 @pytest.mark.parametrize("flags", [0, 1, 2, 12])
