@@ -251,6 +251,25 @@ int quest_decode_step(const quest_cache* cache, const void* k_new, const void* v
                       int32_t out_is_fp16, float* lse, void* workspace, size_t workspace_bytes,
                       void* stream);
 
+/* quest_decode_step for callers that cannot allocate or carry a workspace: code
+ * that runs under HIP graph capture in a harness that forbids hipMalloc, tight
+ * serving loops, test harnesses.  Same arguments, launches and results as
+ * quest_decode_step, but the decode workspace lives in a static device array of
+ * the library (4 MiB per GPU, held until the process ends) instead of caller
+ * memory.  The call allocates and frees nothing.  Shapes whose workspace
+ * (quest_step_workspace_bytes) exceeds 4 MiB are refused with
+ * QUEST_ERR_WORKSPACE.  The call first enqueues a small kernel that zeroes the
+ * arrival counters it is going to use (the array keeps the previous call's
+ * contents).  All calls on one GPU share the one array: calls that overlap in
+ * time on the same GPU (different streams, or graphs replayed concurrently) race;
+ * serialise them, or use quest_decode_step with a workspace per stream.  The
+ * first call on a device looks the array's address up (no stream work); make
+ * that first call outside stream capture. */
+int quest_decode_step_static(const quest_cache* cache, const void* k_new, const void* v_new,
+                             int32_t k_pool_write, const void* q, int32_t k_pages,
+                             float sm_scale, float* scores, int32_t* topk_idx, int32_t* k_eff,
+                             void* out, int32_t out_is_fp16, float* lse, void* stream);
+
 /* Human-readable description of the last error on the calling thread.  Host
  * string owned by the library, valid until the thread's next failing call. */
 const char* quest_last_error(void);

@@ -24,7 +24,7 @@ STATUS_NAMES = {0: "QUEST_OK", -1: "QUEST_ERR_NULL", -2: "QUEST_ERR_SHAPE",
 EXPORTS = ("quest_workspace_bytes", "quest_build_meta", "quest_append_meta", "quest_estimate",
            "quest_append_estimate", "quest_topk", "quest_topk_workspace_bytes", "quest_sparse_decode",
            "quest_select_decode", "quest_step_workspace_bytes", "quest_decode_step",
-           "quest_last_error")
+           "quest_decode_step_static", "quest_last_error")
 
 
 class QuestError(RuntimeError):
@@ -72,6 +72,7 @@ def load():
     lib.quest_step_workspace_bytes.argtypes = [cp, i32, ctypes.POINTER(ctypes.c_size_t)]
     lib.quest_decode_step.argtypes = [cp, vp, vp, i32, vp, i32, f32, vp, vp, vp, vp, i32, vp, vp,
                                       ctypes.c_size_t, vp]
+    lib.quest_decode_step_static.argtypes = [cp, vp, vp, i32, vp, i32, f32, vp, vp, vp, vp, i32, vp, vp]
     for name in EXPORTS[:-1]:
         getattr(lib, name).restype = ctypes.c_int
     lib.quest_last_error.argtypes = []
@@ -192,3 +193,11 @@ def quest_decode_step(cache: Cache, k_new, v_new, k_pool_write, q, k_pages, sm_s
         int(out.dtype == torch.float16), _ptr(lse), _ptr(workspace), ws_bytes, _stream(stream)))
 
 
+
+def quest_decode_step_static(cache: Cache, k_new, v_new, k_pool_write, q, k_pages, sm_scale, scores,
+                             topk_idx, out, k_eff=None, lse=None, stream=None):
+    import torch
+    _check(load().quest_decode_step_static(
+        cache.ref, _ptr(k_new), _ptr(v_new), int(bool(k_pool_write)), _ptr(q), int(k_pages),
+        float(sm_scale), _ptr(scores), _ptr(topk_idx), _ptr(k_eff), _ptr(out),
+        int(out.dtype == torch.float16), _ptr(lse), _stream(stream)))

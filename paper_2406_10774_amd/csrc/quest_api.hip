@@ -263,4 +263,28 @@ int quest_decode_step(const quest_cache* cache, const void* k_new, const void* v
                             (hipStream_t)stream);
 }
 
+int quest_decode_step_static(const quest_cache* cache, const void* k_new, const void* v_new,
+                             int32_t k_pool_write, const void* q, int32_t k_pages, float sm_scale,
+                             float* scores, int32_t* topk_idx, int32_t* k_eff, void* out,
+                             int32_t out_is_fp16, float* lse, void* stream) {
+  int r = check_cache(cache, "quest_decode_step_static");
+  if (r != QUEST_OK) return r;
+  if (cache->k_pool == nullptr || cache->v_pool == nullptr || cache->meta == nullptr ||
+      q == nullptr || scores == nullptr || topk_idx == nullptr || out == nullptr) {
+    set_error("quest_decode_step_static: k_pool, v_pool, meta, q, scores, topk_idx and out must not be NULL");
+    return QUEST_ERR_NULL;
+  }
+  if (k_new != nullptr && k_pool_write && v_new == nullptr) {
+    set_error("quest_decode_step_static: k_pool_write needs v_new");
+    return QUEST_ERR_NULL;
+  }
+  if (k_pages < 1) {
+    set_error("quest_decode_step_static: k_pages must be >= 1 (got %d)", k_pages);
+    return QUEST_ERR_SHAPE;
+  }
+  return launch_decode_step_static(*cache, k_new, v_new, k_pool_write != 0, q, k_pages, sm_scale,
+                                   scores, topk_idx, k_eff, out, out_is_fp16 != 0, lse,
+                                   (hipStream_t)stream);
+}
+
 }  // extern "C"

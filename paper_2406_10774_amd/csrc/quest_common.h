@@ -71,6 +71,10 @@ int launch_decode_step(const quest_cache& c, const void* k_new, const void* v_ne
                        const void* q, int k_pages, float sm_scale, float* scores, int32_t* topk_idx,
                        int32_t* k_eff, void* out, int out_is_fp16, float* lse, void* workspace,
                        size_t workspace_bytes, hipStream_t s);
+int launch_decode_step_static(const quest_cache& c, const void* k_new, const void* v_new,
+                              int k_pool_write, const void* q, int k_pages, float sm_scale,
+                              float* scores, int32_t* topk_idx, int32_t* k_eff, void* out,
+                              int out_is_fp16, float* lse, hipStream_t s);
 
 // -------------------------------------------------------------- device side
 #if defined(__HIPCC__)
