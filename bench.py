@@ -19,6 +19,7 @@ timed on the host cores.
 from __future__ import annotations
 
 import argparse
+import ctypes
 import json
 import math
 import os
@@ -54,6 +55,8 @@ def parse():
                     help="that many copies of the workload's (single) sequence in one batch: the "
                          "throughput regime.  Implies --no-cpu-baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-yardsticks", action="store_true",
+                    help="skip the plain-read and bare-gather kernels timed next to the library's")
     ap.add_argument("--eager", action="store_true", help="also time eager (per-call) launches")
     return ap.parse_args()
 
@@ -278,9 +281,25 @@ def main():
     achieved = dom_bytes / dom_us / 1e3
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                # the counters were collected on the headline configuration only
+                # the counters were collected on the headline configuration only; this run does
+                # not measure them (the profiler cannot run inside it): the figure is the one
+                # recorded under profiles/ for the same kernel and launch shape
                 "traffic": load_traffic(dom) if args.config == 1 and not (
-                    args.batch or args.page_size or args.kv_heads or args.token_budget) else None}
+                    args.batch or args.page_size or args.kv_heads or args.token_budget) else None,
+                "traffic_source": "profiles/hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
+                                  "per dispatch, scaled by a copy kernel of known size)"}
+
+    roofline["frac_of_yardstick"] = None
+    yard = None
+    if not args.no_yardsticks:
+        yard = yardsticks(torch, layers, idx, pt, H, S, D, args.steps)
+        # the dominant kernel against the machine's own rate on its access pattern with no
+        # arithmetic: a plain scan for the estimate, a bare gather for the attention
+        ref = yard["stream_gbps_32mib"] if dom == "quest_append_estimate" else yard["gather_gbps"]
+        if ref:
+            roofline["frac_of_yardstick"] = round(achieved / ref, 4)
+    build = time_build_meta(torch, Q, layers, pt, lens0_dev, lens0, H, S, D)
+    kernels.update(build)
 
     # ---------------------------------------------------------- CPU baseline
     cpu = None
@@ -308,9 +327,107 @@ def main():
         "speedup_vs_own_dense": round(dense_us / us_step, 3),
         "eager_us_per_step": None if eager_us is None else round(eager_us, 3),
         "kernels": kernels, "roofline": roofline, "cpu_baseline": cpu,
+        "yardsticks": yard, "host_nproc": os.cpu_count(),
         "setup_s": round(gen_s, 1),
     }
     print(json.dumps(line))
+
+
+def _graph_us(torch, fn, n, repeats=3):
+    """Median GPU microseconds per call of fn(i), i < n, captured once and replayed."""
+    fn(0)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for i in range(n):
+            fn(i)
+    g.replay()
+    times = []
+    for _ in range(repeats):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        times.append(e0.elapsed_time(e1) * 1e3 / n)
+    return float(np.median(times))
+
+
+def yardsticks(torch, layers, idx, pt, H, S, D, n):
+    """What the machine does on the step's access patterns with no arithmetic, measured in
+    this run on the same buffers (rotating over the layers like the step does): a launch
+    floor, plain scans of the metadata table and of K + V, and a gather of the selected
+    (page, head) blocks through a list in the attention's launch shape."""
+    path = os.path.join(ROOT, "paper_2406_10774_amd", "libquest_yardstick.so")
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: build it with `python -m paper_2406_10774_amd.build`")
+    lib = ctypes.CDLL(path)
+    vp = ctypes.c_void_p
+    lib.yardstick_empty.argtypes = [vp]
+    lib.yardstick_read.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_size_t, ctypes.c_int, vp, vp]
+    lib.yardstick_gather.argtypes = [vp, vp, vp, ctypes.c_int, ctypes.c_int, vp, vp]
+    sink = torch.zeros(4, dtype=torch.int32, device=idx.device)
+    nl = len(layers)
+
+    def stream():
+        return vp(torch.cuda.current_stream().cuda_stream)
+
+    def ok(r):
+        assert r == 0, "yardstick launch failed"
+
+    out = {}
+    out["empty_launch_us"] = round(_graph_us(torch, lambda i: ok(lib.yardstick_empty(stream())), n), 3)
+    meta_bytes = layers[0][2].numel() * 2
+    kv_bytes = layers[0][0].numel() * 2
+    for nt in (0, 1):
+        tag = "_nt" if nt else ""
+        us = _graph_us(torch, lambda i: ok(lib.yardstick_read(
+            vp(layers[i % nl][2].data_ptr()), meta_bytes, None, 0, nt, vp(sink.data_ptr()), stream())), n)
+        out["stream_us_meta" + tag] = round(us, 3)
+        out["stream_gbps_meta" + tag] = round(meta_bytes / us / 1e3, 1)
+        us = _graph_us(torch, lambda i: ok(lib.yardstick_read(
+            vp(layers[i % nl][0].data_ptr()), kv_bytes, vp(layers[i % nl][1].data_ptr()), kv_bytes, nt,
+            vp(sink.data_ptr()), stream())), max(4, n // 8))
+        out["stream_us_kv" + tag] = round(us, 3)
+        out["stream_gbps_kv" + tag] = round(2 * kv_bytes / us / 1e3, 1)
+    out["meta_table_mib"] = round(meta_bytes / 2 ** 20, 1)
+    out["kv_pools_mib"] = round(2 * kv_bytes / 2 ** 20, 1)
+    # the better of the two load kinds is the yardstick (the library's kernels use the
+    # non-temporal kind); named for the sizes they have at the headline configuration
+    out["stream_gbps_32mib"] = max(out["stream_gbps_meta"], out["stream_gbps_meta_nt"])
+    out["stream_gbps_512mib"] = max(out["stream_gbps_kv"], out["stream_gbps_kv_nt"])
+    out["gather_gbps"] = None
+    if S * D * 2 == 4096:
+        # the page list of the last step, as block ids into the pools: (physical page, head)
+        B, Hk, K = idx.shape
+        lp = idx.clamp(min=0).long()                                    # [B][H][K]
+        phys = torch.gather(pt.long().unsqueeze(1).expand(B, Hk, pt.shape[1]), 2, lp)
+        blocks = (phys * Hk + torch.arange(Hk, device=idx.device).view(1, Hk, 1))[idx >= 0]
+        blocks = blocks.to(torch.int32).contiguous()
+        n_blk = int(blocks.numel())
+        for nt in (0, 1):
+            us = _graph_us(torch, lambda i: ok(lib.yardstick_gather(
+                vp(layers[i % nl][0].data_ptr()), vp(layers[i % nl][1].data_ptr()),
+                vp(blocks.data_ptr()), n_blk, nt, vp(sink.data_ptr()), stream())), n)
+            out["gather_us" + ("_nt" if nt else "")] = round(us, 3)
+            out["gather_gbps" + ("_nt" if nt else "_plain")] = round(n_blk * 8192 / us / 1e3, 1)
+        out["gather_blocks"] = n_blk
+        out["gather_gbps"] = max(out["gather_gbps_plain"], out["gather_gbps_nt"])
+    return out
+
+
+def time_build_meta(torch, Q, layers, pt, lens_dev, lens, H, S, D):
+    """quest_build_meta over all pages of every layer buffer (the prefill side of the path):
+    microseconds per call and GB/s on the keys it has to read."""
+    caches = [Q.Cache(kp, vp_, meta, pt, lens_dev) for kp, vp_, meta in layers]
+    us = _graph_us(torch, lambda i: Q.quest_build_meta(caches[i % len(caches)]), max(len(caches), 8))
+    pages = int(sum(-(-int(x) // S) for x in lens))
+    read = H * pages * S * D * 2
+    written = H * pages * 2 * D * 2
+    return {"build_meta_us": round(us, 3), "build_meta_gbps": round(read / us / 1e3, 1),
+            "build_meta_read_written_gbps": round((read + written) / us / 1e3, 1),
+            "build_meta_read_mib": round(read / 2 ** 20, 1)}
 
 
 def load_traffic(kernel):

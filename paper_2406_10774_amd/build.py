@@ -28,9 +28,28 @@ def sources():
     return sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hip"))
 
 
+YARDSTICK_SRC = os.path.join(PKG_DIR, "bench_kernels", "yardstick.hip")
+YARDSTICK_LIB = os.path.join(PKG_DIR, "libquest_yardstick.so")
+
+
+def build_yardstick(verbose: bool = True) -> str:
+    """The benchmark's own kernels (plain reads, a bare gather): a library of its own."""
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    tmp = YARDSTICK_LIB + ".tmp"
+    r = subprocess.run([hipcc, *HIPCC_FLAGS, "-shared", YARDSTICK_SRC, "-o", tmp],
+                       capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed on {YARDSTICK_SRC}:\n{r.stderr}")
+    os.replace(tmp, YARDSTICK_LIB)
+    if verbose:
+        print(f"built {YARDSTICK_LIB}")
+    return YARDSTICK_LIB
+
+
 def build(verbose: bool = True) -> str:
     hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
     os.makedirs(BUILD_DIR, exist_ok=True)
+    build_yardstick(verbose)
 
     def compile_one(src):
         obj = os.path.join(BUILD_DIR, os.path.basename(src)[:-4] + ".o")

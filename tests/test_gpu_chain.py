@@ -106,12 +106,13 @@ def run_decode_steps(w, steps, permute, flags, group=1):
     and page list) and against the oracle (attention within tolerance).  group > 1:
     grouped-query attention, w describes the KV heads."""
     import dataclasses
-    from gpu_util import Layer
+    from gpu_util import Layer, check_selection
     S, D = w.page_size, w.head_dim
     wq = dataclasses.replace(w, num_heads=w.num_heads * group)
     table, N = synth.make_page_table(w, permute=permute)
     k_pool, v_pool, _ = synth.fill_pools(w, table, N)
     lens = np.array(w.seq_lens, np.int32)
+    meta = O.build_meta(k_pool, table, lens)
     one = Layer(k_pool, v_pool, table, lens, flags=flags, num_q_heads=wq.num_heads)   # one call
     ref = Layer(k_pool, v_pool, table, lens, flags=flags & 12,
                 num_q_heads=wq.num_heads)               # separate calls, same selection policy
@@ -129,6 +130,7 @@ def run_decode_steps(w, steps, permute, flags, group=1):
             ref.set_seq_lens(cur)
             ref.append(k_new, v_new, write=True)
             O.append_kv(k_pool, v_pool, k_new, v_new, table, cur)
+            meta = O.append_meta(meta, k_new, table, cur, S)
         sc1, idx1, keff1, out1, lse1 = one.step(k_new if append else None,
                                                 v_new if append else None, q, w.k_pages)
         sc0 = ref.estimate(q)
@@ -137,6 +139,8 @@ def run_decode_steps(w, steps, permute, flags, group=1):
             P = -(-int(cur[b]) // S)
             assert np.array_equal(sc1[b, :, :P].view(np.uint32), sc0[b, :, :P].view(np.uint32)), step
         assert np.array_equal(idx1, idx0) and np.array_equal(keff1, keff0), step
+        if not flags & 12:      # and directly against the selection the oracle's scores imply
+            check_selection(idx1, O.estimate(meta, q, table, cur, S), cur, S, w.k_pages)
         if flags & 4:
             assert (idx1[:, :, 0] == 0).all(), step
         if flags & 8:

@@ -41,7 +41,7 @@ def chain_at_full_size(w, k_pages_list, steps, use_step_call):
         layer.set_seq_lens(cur)
         O.append_kv(k_pool, v_pool, k_new, v_new, table, cur)
         meta = O.append_meta(meta, k_new, table, cur, S)
-        if use_step_call:
+        if use_step_call(step) if callable(use_step_call) else use_step_call:
             got_sc, got_idx, keff, got, lse = layer.step(k_new, v_new, q, k_pages)
         else:
             layer.append(k_new, v_new, write=True)
@@ -66,11 +66,14 @@ def chain_at_full_size(w, k_pages_list, steps, use_step_call):
 
 
 def test_config2_128k_context_budget_sweep():
-    chain_at_full_size(synth.workload(2), k_pages_list=(64, 256, 512), steps=3, use_step_call=False)
+    # every budget once through the separate calls, once through quest_decode_step
+    chain_at_full_size(synth.workload(2), k_pages_list=(64, 256, 512), steps=6,
+                       use_step_call=lambda step: step >= 3)
 
 
 def test_config3_ragged_batch16():
-    chain_at_full_size(synth.workload(3), k_pages_list=(128,), steps=2, use_step_call=True)
+    # 9 steps: half of the sequences open a new page on the way
+    chain_at_full_size(synth.workload(3), k_pages_list=(128,), steps=9, use_step_call=True)
 
 
 def test_config4_512k_context():

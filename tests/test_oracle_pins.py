@@ -321,6 +321,43 @@ def test_topk_forced_pages(keep_first, keep_newest):
                 assert (idx[b, h, keff[b]:] == -1).all()
 
 
+@pytest.mark.parametrize("keep_first,keep_newest", [(True, False), (False, True), (True, True)])
+def test_topk_forced_pages_rank_above_infinite_scores(keep_first, keep_newest):
+    """Rows that hold real +inf (and -inf) scores: a forced page still ranks above every
+    score, +inf included, so with K smaller than forced + infinite pages the forced ones are
+    in and the infinite ones compete for what is left, lowest page first.  Built without the
+    oracle's ranking: forced pages out, repeated arg-max (first maximum wins) over the rest."""
+    S = 16
+    lens = np.array([16 * 11 + 5], np.int32)                     # 12 pages
+    P = 12
+    sc = np.array([[[3.0, np.inf, -np.inf, 7.0, np.inf, 2.0, 9.0, -1.0, np.inf, 4.0, 6.0, -np.inf],
+                    [-np.inf, 1.0, np.inf, 1.0, 5.0, np.inf, 0.0, 2.0, 8.0, -np.inf, 3.0, np.inf]]])
+    for K in (1, 2, 3, 4, 5, 9, 12, 20):
+        idx, keff = O.topk(sc, lens, S, K, keep_first=keep_first, keep_newest=keep_newest)
+        forced = sorted(set(([0] if keep_first else []) + ([P - 1] if keep_newest else [])))[:min(K, P)]
+        for h in range(2):
+            rest = [p for p in range(P) if p not in forced]
+            left = min(K, P) - len(forced)
+            vals = [float(sc[0, h, p]) for p in rest]
+            fill = []
+            for _ in range(left):                                # repeated arg-max, explicit loops
+                best = None
+                for i, v in enumerate(vals):
+                    if i in fill:
+                        continue
+                    if best is None or v > vals[best]:
+                        best = i
+                fill.append(best)
+            want = sorted(forced + [rest[i] for i in fill])
+            assert list(idx[0, h, :keff[0]]) == want, (K, h)
+            assert (idx[0, h, keff[0]:] == -1).all()
+    # the case that tells the two readings apart: K = 2, page 0 forced (score 3.0) next to
+    # three pages with score +inf: the list is the forced page and the first infinite page
+    if keep_first and not keep_newest:
+        idx, _ = O.topk(sc, lens, S, 2, keep_first=True)
+        assert list(idx[0, 0]) == [0, 1]
+
+
 # ------------------------------------------------------------------ attention
 def brute_attention(k_pool, v_pool, q, table, lens, pages_of, scale):
     """Explicit-loop softmax attention over the listed pages, Python floats."""
@@ -406,7 +443,7 @@ def test_attention_degenerate_cases():
 def test_loaded_fraction_matches_the_papers_worked_example(repo_root):
     rows = [l.split() for l in open(os.path.join(repo_root, "tests/golden/loaded_fraction.txt"))
             if l.strip() and not l.startswith("#")]
-    assert len(rows) == 2
+    assert len(rows) == 1
     for s, k, p, factor in rows:
         assert 1.0 / O.loaded_fraction(int(s), int(k), int(p)) == pytest.approx(float(factor))
 

@@ -92,6 +92,19 @@ def topk_forced_pages_forgotten(scores, seq_lens, page_size, k_pages, keep_first
     return O_topk(scores, seq_lens, page_size, k_pages)
 
 
+def topk_forced_pages_tie_with_infinite_scores(scores, seq_lens, page_size, k_pages, keep_first=False,
+                                               keep_newest=False):
+    """Forced pages given the score +inf and ranked like any other score."""
+    s = np.array(scores, np.float64)
+    for b in range(s.shape[0]):
+        P = O.num_pages(seq_lens[b], page_size)
+        if keep_first:
+            s[b, :, 0] = np.inf
+        if keep_newest:
+            s[b, :, P - 1] = np.inf
+    return O_topk(s, seq_lens, page_size, k_pages)
+
+
 def build_meta_includes_stale_slots(k_pool, page_table, seq_lens, meta_init=None):
     S = k_pool.shape[2]
     full = np.array([O.num_pages(L, S) * S for L in seq_lens], np.int32)
@@ -168,6 +181,8 @@ CASES = [
     ("topk", topk_reads_past_the_valid_pages, pins.test_topk_special_cases, ()),
     ("topk", topk_signed_zeros_differ, pins.test_topk_special_cases, ()),
     ("topk", topk_forced_pages_forgotten, pins.test_topk_forced_pages, (True, True)),
+    ("topk", topk_forced_pages_tie_with_infinite_scores,
+     pins.test_topk_forced_pages_rank_above_infinite_scores, (False, True)),
     ("build_meta", build_meta_includes_stale_slots, pins.test_build_meta_equals_exhaustive_scan, (0,)),
     ("build_meta", build_meta_swaps_min_and_max, pins.test_build_meta_equals_exhaustive_scan, (1,)),
     ("build_meta", build_meta_swaps_min_and_max, pins.test_meta_bounds_every_token_and_ignores_unmapped, ()),
