@@ -153,9 +153,39 @@ __device__ __forceinline__ uint4 key_max8(uint4 a, uint4 b) {
   return make_uint4(key_max2(a.x, b.x), key_max2(a.y, b.y), key_max2(a.z, b.z), key_max2(a.w, b.w));
 }
 
-__device__ __forceinline__ uint4 shfl_xor16(uint4 v, int mask) {
-  return make_uint4(__shfl_xor(v.x, mask), __shfl_xor(v.y, mask), __shfl_xor(v.z, mask),
-                    __shfl_xor(v.w, mask));
+// The value of the lane 16 (32) lanes away next to this lane's own, without going through
+// LDS: v_permlane16_swap / v_permlane32_swap exchange the odd rows (the upper half) of
+// one register with the even rows (the lower half) of another.  With both registers
+// holding v, the pair (first, second) is (v of the even row / lower half, v of the odd row
+// / upper half) in every lane of the two: a commutative op(first, second) is the
+// reduction over the pair, the same bits in both lanes.
+struct LanePair {
+  uint32_t first, second;
+};
+__device__ __forceinline__ LanePair pair_across16(uint32_t v) {
+  const auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+  return {r[0], r[1]};
+}
+__device__ __forceinline__ LanePair pair_across32(uint32_t v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+  return {r[0], r[1]};
+}
+// min / max over the four DPP rows of packed 16-bit order keys; every lane gets the result
+__device__ __forceinline__ uint32_t rows_key_min2(uint32_t v) {
+  LanePair p = pair_across16(v);
+  p = pair_across32(key_min2(p.first, p.second));
+  return key_min2(p.first, p.second);
+}
+__device__ __forceinline__ uint32_t rows_key_max2(uint32_t v) {
+  LanePair p = pair_across16(v);
+  p = pair_across32(key_max2(p.first, p.second));
+  return key_max2(p.first, p.second);
+}
+__device__ __forceinline__ uint4 rows_key_min8(uint4 v) {
+  return make_uint4(rows_key_min2(v.x), rows_key_min2(v.y), rows_key_min2(v.z), rows_key_min2(v.w));
+}
+__device__ __forceinline__ uint4 rows_key_max8(uint4 v) {
+  return make_uint4(rows_key_max2(v.x), rows_key_max2(v.y), rows_key_max2(v.z), rows_key_max2(v.w));
 }
 
 __device__ __forceinline__ int ceil_div(int a, int b) { return (a + b - 1) / b; }

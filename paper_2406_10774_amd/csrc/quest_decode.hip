@@ -264,8 +264,7 @@ __global__ __launch_bounds__(kWaves* kWave) void decode_split_kernel(const Decod
   // the four DPP rows of the wave, then the four waves of the group
 #pragma unroll
   for (int g = 0; g < kG; ++g) {
-    merge_lanes(st[g], 16);
-    merge_lanes(st[g], 32);
+    merge_rows(st[g]);
     if (lane < 16) {
 #pragma unroll
       for (int j = 0; j < 8; ++j) sm_acc[wave][g][c * 8 + j] = st[g].acc[j];

@@ -134,17 +134,28 @@ __device__ __forceinline__ void fold_group(Softmax (&st)[kG], PageRegsT<kLoads>&
   }
 }
 
-// merge the state held by lane ^ mask into this lane's
-__device__ __forceinline__ void merge_lanes(Softmax& st, int mask) {
-  const float m_o = __shfl_xor(st.m, mask);
-  const float l_o = __shfl_xor(st.l, mask);
-  const float m_n = fmaxf(st.m, m_o);
-  const float a = __builtin_amdgcn_exp2f(st.m - m_n);
-  const float b = __builtin_amdgcn_exp2f(m_o - m_n);
-  st.l = st.l * a + l_o * b;
+// Merge the online-softmax states of the wave's four DPP rows (lanes 16 apart, then lanes
+// 32 apart); every lane ends up with the merged state of its channels.
+__device__ __forceinline__ float as_f(uint32_t u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ uint32_t as_u(float f) { return __builtin_bit_cast(uint32_t, f); }
+template <bool kAcross32>
+__device__ __forceinline__ void merge_rows_step(Softmax& st) {
+  auto pair = [](float v) { return kAcross32 ? pair_across32(as_u(v)) : pair_across16(as_u(v)); };
+  const LanePair m = pair(st.m), l = pair(st.l);
+  const float m_n = fmaxf(as_f(m.first), as_f(m.second));
+  const float a = __builtin_amdgcn_exp2f(as_f(m.first) - m_n);
+  const float b = __builtin_amdgcn_exp2f(as_f(m.second) - m_n);
+  st.l = as_f(l.first) * a + as_f(l.second) * b;
 #pragma unroll
-  for (int j = 0; j < 8; ++j) st.acc[j] = st.acc[j] * a + __shfl_xor(st.acc[j], mask) * b;
+  for (int j = 0; j < 8; ++j) {
+    const LanePair p = pair(st.acc[j]);
+    st.acc[j] = as_f(p.first) * a + as_f(p.second) * b;
+  }
   st.m = m_n;
+}
+__device__ __forceinline__ void merge_rows(Softmax& st) {
+  merge_rows_step<false>(st);
+  merge_rows_step<true>(st);
 }
 
 __device__ __forceinline__ void store_out(void* out, int out_is_fp16, size_t idx, float v) {
