@@ -98,7 +98,14 @@ def main():
     # ---------------------------------------------------------------- inputs
     t0 = time.time()
     table, N = synth.make_page_table(w, permute=False)
-    k_pool, v_pool, _ = synth.fill_pools(w, table, N, stale_fill=0.0, threads=16)
+    last = [time.time()]
+
+    def progress(done, total):                            # long set-ups say that they are alive
+        if time.time() - last[0] > 20 or done == total:
+            last[0] = time.time()
+            print(f"bench.py: generated {done} of {total} (sequence, head) pairs", file=sys.stderr, flush=True)
+
+    k_pool, v_pool, _ = synth.fill_pools(w, table, N, stale_fill=0.0, threads=16, progress=progress)
     lens0 = np.array(w.seq_lens, np.int32)
 
     def dev16(a):
@@ -111,7 +118,12 @@ def main():
     lens_dev = torch.from_numpy(lens_steps).to(dev)
     lens0_dev = torch.from_numpy(lens0).to(dev)
     q_all = dev16(np.stack([synth.gen_query(wq, i) for i in range(n_total)]))
-    new_kv = [synth.gen_new_token(w, i) for i in range(n_total)]
+    new_kv = []
+    for i in range(n_total):
+        new_kv.append(synth.gen_new_token(w, i))
+        if time.time() - last[0] > 20:
+            last[0] = time.time()
+            print(f"bench.py: new tokens of step {i + 1} of {n_total} generated", file=sys.stderr, flush=True)
     kn_all = dev16(np.stack([k for k, _ in new_kv]))
     vn_all = dev16(np.stack([v for _, v in new_kv]))
 
@@ -122,6 +134,9 @@ def main():
         meta = torch.zeros((H, N, 2, D), dtype=torch.float16, device=dev)
         Q.quest_build_meta(Q.Cache(kp, vp, meta, pt, lens0_dev))
         layers.append((kp, vp, meta))
+        if time.time() - last[0] > 20:
+            last[0] = time.time()
+            print(f"bench.py: layer buffer {l + 1} of {n_layers} on the device", file=sys.stderr, flush=True)
     caches = [Q.Cache(*layers[i % n_layers], pt, lens_dev[i], num_heads=Hq) for i in range(n_total)]
     scores = torch.zeros((B, H, table.shape[1]), dtype=torch.float32, device=dev)
     idx = torch.zeros((B, H, K), dtype=torch.int32, device=dev)

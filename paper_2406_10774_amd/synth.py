@@ -184,12 +184,13 @@ def make_page_table(w: Workload, permute: bool, spare_pages: int = 2):
 
 
 def fill_pools(w: Workload, page_table: np.ndarray, num_phys_pages: int,
-               stale_fill: float = float("nan"), threads: int = 8):
+               stale_fill: float = float("nan"), threads: int = 8, progress=None):
     """Generate K/V for every (sequence, head) and scatter into paged pools.
 
     Slots that hold no valid token (tail of a partial last page, pages reserved
     for later decode steps, spare pages) are filled with `stale_fill` (NaN by
     default) so that any read of a stale slot poisons the result.
+    progress(done, total), if given, is called as (sequence, head) pairs are finished.
     Returns (k_pool, v_pool, q0) with q0 = the step-0 query fp16 [B][H][D]."""
     H, S, D = w.num_heads, w.page_size, w.head_dim
     k_pool = np.full((num_phys_pages, H, S, D), stale_fill, np.float16)
@@ -214,8 +215,12 @@ def fill_pools(w: Workload, page_table: np.ndarray, num_phys_pages: int,
     jobs = [(b, h) for b in range(w.batch) for h in range(H)]
     if threads > 1 and len(jobs) > 1:
         with ThreadPoolExecutor(max_workers=threads) as ex:
-            list(ex.map(one, jobs))
+            for n, _ in enumerate(ex.map(one, jobs)):
+                if progress is not None:
+                    progress(n + 1, len(jobs))
     else:
-        for j in jobs:
+        for n, j in enumerate(jobs):
             one(j)
+            if progress is not None:
+                progress(n + 1, len(jobs))
     return k_pool, v_pool, q0
