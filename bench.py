@@ -267,6 +267,13 @@ def main():
     k_appest = kernel_us(lambda i: Q.quest_append_estimate(caches[i], kn_all[i], vn_all[i], True,
                                                            q_all[i], scores))
     k_topk = kernel_us(lambda i: Q.quest_topk(caches[i], scores, K, idx, None))
+    # rows long enough for the selection in two stages (two launches: per-chunk candidates, then
+    # the K best of those), which quest_topk runs when the caller brings the workspace for it
+    topk_ws_bytes = Q.quest_topk_workspace_bytes(caches[0], K)
+    k_topk2 = None
+    if topk_ws_bytes:
+        topk_ws = torch.zeros(topk_ws_bytes, dtype=torch.uint8, device=dev)
+        k_topk2 = kernel_us(lambda i: Q.quest_topk(caches[i], scores, K, idx, None, topk_ws))
     k_dec = kernel_us(lambda i: Q.quest_sparse_decode(caches[i], q_all[i], idx, K, scale, out, None, ws))
     k_app = kernel_us(lambda i: Q.quest_append_meta(caches[i], kn_all[i], vn_all[i], True))
     k_dense = kernel_us(lambda i: Q.quest_sparse_decode(caches[i], q_all[i], None, 0, scale, out,
@@ -282,6 +289,7 @@ def main():
         "append_estimate_us": round(k_appest, 3),
         "append_estimate_gbps": round(meta_bytes / k_appest / 1e3, 1),
         "topk_us": round(k_topk, 3),
+        "topk_two_stage_us": None if k_topk2 is None else round(k_topk2, 3),
         "sparse_decode_us": round(k_dec, 3), "sparse_decode_gbps": round(kv_bytes / k_dec / 1e3, 1),
         "select_decode_us": round(k_seldec, 3) if selects_inside else None,
         "select_decode_gbps": round((kv_bytes + score_bytes) / k_seldec / 1e3, 1) if selects_inside else None,

@@ -154,7 +154,7 @@ __global__ __launch_bounds__(kWaves* kWave) void decode_split_kernel(const Decod
     };
     topk_block_put<kWaves * kWave, kSelItems>(
         sm_topk, a.scores + row * a.max_pages, a.seq_lens + b, a.max_pages, a.k_pages,
-        [&](int pos, int page, int j) {
+        [&](int pos, int page, int j, float) {
           int phys = 0;
           if (j >= 0) {
 #pragma unroll

@@ -124,9 +124,12 @@ struct WholeRow {
 
 // Selection for one row of scores by one work-group of kThreads threads (all of
 // them must call).  shape(seq_len) describes the row (it has room for max_pages
-// entries); put(position, page, j) receives the list: positions 0 .. k_pages-1, pages
-// ascending, -1 past the K_b selected ones; j >= 0 says that the page is the calling
-// thread's j-th one (page == threadIdx.x * kItems + j), j < 0 that it is not.
+// entries); put(position, page, j, score) receives the list: positions 0 .. k_pages-1,
+// pages ascending, -1 past the K_b selected ones; j >= 0 says that the page is the calling
+// thread's j-th one (page == threadIdx.x * kItems + j) and `score` its score as loaded,
+// j < 0 that it is not (then `score` carries nothing).  A put that needs per-page data
+// takes it from what the thread already holds whenever j >= 0: a load issued from inside
+// put is waited for before the next page's put starts.
 // after_loads() is called once, right after the loads of the scores have been issued:
 // the place for loads the caller wants in flight behind them.
 template <int kThreads, int kItems, class Put, class Shape, class AfterLoads>
@@ -166,7 +169,7 @@ __device__ __forceinline__ void topk_block_put(TopkShared<kThreads>& sm,
   const int K = min(k_pages, num_pages);
   if (tid == 0 && k_eff_slot != nullptr) *k_eff_slot = K;
   if (K == num_pages) {  // everything is selected: identity list, padded with -1
-    for (int i = tid; i < k_pages; i += kThreads) put(i, i < K ? i : -1, -1);
+    for (int i = tid; i < k_pages; i += kThreads) put(i, i < K ? i : -1, -1, 0.f);
     return;
   }
 
@@ -176,8 +179,8 @@ __device__ __forceinline__ void topk_block_put(TopkShared<kThreads>& sm,
   const ForcedPages forced = forced_pages(row_shape.policy, num_pages);
   if (forced.count >= K) {  // K is 1 or 2 here: the list is the forced pages, lowest first
     if (tid == 0) {
-      put(0, forced.first ? 0 : num_pages - 1, -1);
-      if (K == 2) put(1, num_pages - 1, -1);
+      put(0, forced.first ? 0 : num_pages - 1, -1, 0.f);
+      if (K == 2) put(1, num_pages - 1, -1, 0.f);
     }
     return;
   }
@@ -270,7 +273,7 @@ __device__ __forceinline__ void topk_block_put(TopkShared<kThreads>& sm,
 #pragma unroll
   for (int j = 0; j < kItems; ++j) {
     const bool sel = gt[j] || (eq[j] && eq_before < need);
-    if (sel) put(gt_before + min(eq_before, need), base + j, j);
+    if (sel) put(gt_before + min(eq_before, need), base + j, j, raw[j]);
     gt_before += gt[j];
     eq_before += eq[j];
   }
@@ -284,7 +287,7 @@ __device__ __forceinline__ void topk_block(TopkShared<kThreads>& sm, const float
                                            int32_t* __restrict__ k_eff_slot, int page_shift,
                                            int policy) {
   topk_block_put<kThreads, kItems>(
-      sm, row, seq_len_ptr, max_pages, k_pages, [out](int pos, int page, int) { out[pos] = page; },
+      sm, row, seq_len_ptr, max_pages, k_pages, [out](int pos, int page, int, float) { out[pos] = page; },
       k_eff_slot, WholeRow{page_shift, policy}, [] {});
 }
 
