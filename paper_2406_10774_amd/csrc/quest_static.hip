@@ -73,7 +73,9 @@ int launch_decode_step_static(const quest_cache& c, const void* k_new, const voi
   void* ws = nullptr;
   int r = scratch_pointer(&ws);
   if (r != QUEST_OK) return r;
-  const size_t words = decode_counter_bytes(c) / sizeof(uint32_t);  // <= need <= kScratchBytes
+  // counters exist when the attention runs in several splits; they are then the first
+  // bytes of its workspace (<= need <= kScratchBytes)
+  const size_t words = decode_workspace_bytes(c, k_pages) ? decode_counter_bytes(c) / sizeof(uint32_t) : 0;
   if (need > 0 && words > 0) {
     hipLaunchKernelGGL(clear_words_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, s,
                        (uint32_t*)ws, words);

@@ -11,10 +11,12 @@
 // too long for that, the selection runs as its own launch (three launches).
 //
 // A single launch for the whole step (teams of work-groups per head that wait for
-// each other through L2) was built and measured as well: 24.2 us against 23.5 us
-// for these two launches at 32 heads / 32k context, because inside one launch the
-// selection shares compute units with streaming work-groups; it also needed the
-// whole grid resident at once.  It is not part of the library.
+// each other through L2) was built and measured twice: 24.2 us against 23.5 us for
+// these two launches at 32 heads / 32k context in its first form, 28.5 us against
+// 21.6 us in its second (the estimate's pages spread over the attention launch's 256
+// work-groups).  The metadata scan wants tens of thousands of waves, the attention
+// part 256 work-groups of 8; one grid cannot be both, and the wait needs the whole grid
+// resident at once.  It is not part of the library.
 #include "quest_common.h"
 
 namespace quest {
