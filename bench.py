@@ -65,7 +65,8 @@ def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (--gpus 1); the path shards over "
-              "heads/sequences without communication, see DESIGN.md", file=sys.stderr)
+              "heads and sequences without communication, each GPU runs this same step on its share",
+              file=sys.stderr)
         sys.exit(2)
     import torch
     from paper_2406_10774_amd import binding as Q, synth
