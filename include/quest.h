@@ -17,7 +17,9 @@
  *
  * Conventions for every entry point
  *   - All data pointers are DEVICE pointers owned by the caller.  The library
- *     never allocates or frees device memory and keeps no state between calls.
+ *     never allocates or frees device memory and keeps no state between calls
+ *     (quest_decode_step_static alone works in a static device array of the
+ *     library instead of a caller's workspace: see there).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls only enqueue work on that stream; they never synchronise.
  *   - The return value is a quest_status; 0 means "enqueued".  Only facts the
@@ -82,9 +84,10 @@ typedef enum quest_status {
  *    attention launch select its pages (see there; changes no result except
  *    the rounding of out / lse).
  *  QUEST_FLAG_DEVICE_FENCES: work-groups that exchange partial results inside a
- *    launch always use device-scope release/acquire fences, as they do on their
- *    own when they find themselves on different dies (for testing that path;
- *    changes no result).
+ *    launch put device-scope release/acquire fences around their arrival
+ *    counter (the textbook form of the hand-over; by default the results
+ *    travel through device-scope stores and loads and need no fence).  For
+ *    testing that path: slower, changes no result.
  *  QUEST_FLAG_KEEP_FIRST_PAGE, QUEST_FLAG_KEEP_NEWEST_PAGE: selection policy of
  *    quest_topk and quest_decode_step.  The paper selects purely by score
  *    (Section 3.4) and that is the default; with these flags logical page 0
