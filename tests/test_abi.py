@@ -47,6 +47,32 @@ def test_workspace_bytes_is_pure_and_consistent():
     assert lib.quest_workspace_bytes(ctypes.byref(c), 128, None) == -1
 
 
+def test_topk_workspace_bytes_follows_the_two_stage_rule():
+    """quest.h: rows of 16384 pages or more are selected in two stages, a 4096-page chunk
+    keeping its best k_pages as (score, page) candidates, while a row has at most 8192
+    of them and they are fewer than half of the row; everything else needs no workspace."""
+    lib = binding.load()
+    out = ctypes.c_size_t(7)
+
+    def need(max_pages, k_pages, **kw):
+        c = make_cache(max_pages_per_seq=max_pages, **kw)
+        assert lib.quest_topk_workspace_bytes(ctypes.byref(c), k_pages, ctypes.byref(out)) == 0
+        return out.value
+
+    heads = make_cache().num_heads
+    assert need(16383, 64) == 0                                   # short rows: one work-group per row
+    assert need(16384, 64) == heads * 4 * 64 * 8                  # 4 chunks
+    assert need(32769, 256) == heads * 9 * 256 * 8                # the ninth chunk holds one page
+    assert need(32769, 256, batch=3) == 3 * heads * 9 * 256 * 8
+    assert need(32769, 1024) == 0                                 # 9216 candidates: too many
+    assert need(65535, 512) == heads * 16 * 512 * 8
+    assert need(65535, 4097) == 0                                 # more than a chunk holds
+    assert need(16384, 4096) == 0                                 # candidates would be the whole row
+    c = make_cache(max_pages_per_seq=32769)
+    assert lib.quest_topk_workspace_bytes(ctypes.byref(c), 256, None) == -1
+    assert lib.quest_topk_workspace_bytes(ctypes.byref(c), 0, ctypes.byref(out)) == 0 and out.value == 0
+
+
 @pytest.mark.parametrize("kw,status", [
     (dict(head_dim=64), -3), (dict(page_size=24), -3), (dict(page_size=128), -3), (dict(batch=0), -2),
     (dict(num_heads=70000), -2), (dict(page_table=None), -1), (dict(seq_lens=None), -1),
