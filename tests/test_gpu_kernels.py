@@ -271,6 +271,72 @@ def test_topk_key_ranges(max_pages):
                 assert np.array_equal(got[0, h], want[0, h]), (max_pages, policy, k_pages, h)
 
 
+def _random_scores(rng, shape, kind):
+    n = shape[-1]
+    if kind == "normal":
+        return (rng.standard_normal(shape) * 30 + 200).astype(np.float32)
+    if kind == "signs":            # values of both signs over several powers of two, as the
+        x = rng.standard_normal(shape) * 600 + 250          # criticality scores of a long context
+        return x.astype(np.float32)
+    if kind == "heavy":            # a few far outliers stretch the range
+        x = rng.standard_normal(shape).astype(np.float32)
+        x[..., rng.integers(0, n, max(1, n // 97))] *= 1e6
+        return x
+    if kind == "ties":             # few distinct values
+        return rng.integers(-3, 4, shape).astype(np.float32)
+    if kind == "tiny":             # subnormals and zeros of both signs
+        x = (rng.integers(-20, 21, shape) * 1e-42).astype(np.float32)
+        x[..., ::5] = -0.0
+        return x
+    if kind == "inf":
+        x = rng.standard_normal(shape).astype(np.float32)
+        x[..., rng.integers(0, n, max(1, n // 50))] = np.inf
+        x[..., rng.integers(0, n, max(1, n // 50))] = -np.inf
+        return x
+    raise AssertionError(kind)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_topk_randomised_shapes(seed):
+    """Row lengths, sequence lengths, budgets, policy flags and score distributions drawn
+    at random (seeded): every list equals the oracle's, with and without a workspace."""
+    import torch
+    from paper_2406_10774_amd import binding as Q
+    dev = "cuda:0"
+    rng = np.random.default_rng(1000 + seed)
+    kinds = ("normal", "signs", "heavy", "ties", "tiny", "inf")
+    for case in range(8):
+        S = int(rng.choice([8, 16, 32, 64]))
+        B, H = int(rng.integers(1, 4)), int(rng.integers(1, 5))
+        # mostly rows one work-group handles in registers; now and then a two-stage size
+        max_pages = int(rng.integers(16384, 21000)) if case == 7 else int(
+            rng.choice([rng.integers(1, 70), rng.integers(70, 2100), rng.integers(2100, 9000)]))
+        lens = rng.integers(1, max_pages * S + 1, B).astype(np.int32)
+        lens[rng.integers(0, B)] = max_pages * S - int(rng.integers(0, S))      # one full row
+        k_pages = int(rng.choice([1, 2, rng.integers(1, max_pages + 2), rng.integers(1, 300)]))
+        policy = int(rng.choice([0, 0, 4, 8, 12]))
+        sc = np.empty((B, H, max_pages), np.float32)
+        for b in range(B):
+            for h in range(H):
+                sc[b, h] = _random_scores(rng, (max_pages,), str(rng.choice(kinds)))
+        dummy = torch.zeros((1, H, S, 128), dtype=torch.float16, device=dev)
+        meta = torch.zeros((H, 1, 2, 128), dtype=torch.float16, device=dev)
+        pt = torch.zeros((B, max_pages), dtype=torch.int32, device=dev)
+        cache = Q.Cache(dummy, dummy, meta, pt, torch.from_numpy(lens).to(dev), flags=policy)
+        want, want_keff = O.topk(sc, lens, S, k_pages, keep_first=bool(policy & 4),
+                                 keep_newest=bool(policy & 8))
+        scd = torch.from_numpy(sc).to(dev)
+        ws_bytes = Q.quest_topk_workspace_bytes(cache, k_pages)
+        for with_ws in ((False, True) if ws_bytes else (False,)):
+            ws = torch.zeros(ws_bytes // 4, dtype=torch.int32, device=dev) if with_ws else None
+            idx = torch.full((B, H, k_pages), -7, dtype=torch.int32, device=dev)
+            keff = torch.full((B,), -7, dtype=torch.int32, device=dev)
+            Q.quest_topk(cache, scd, k_pages, idx, keff, workspace=ws)
+            what = (seed, case, S, B, H, max_pages, lens.tolist(), k_pages, policy, with_ws)
+            assert np.array_equal(keff.cpu().numpy(), want_keff), what
+            assert np.array_equal(idx.cpu().numpy(), want), what
+
+
 @pytest.mark.parametrize("policy", [4, 8, 12])
 @pytest.mark.parametrize("max_pages,lens", [
     (210, (1, 16 * 3 + 7, 16 * 203 + 5, 16 * 2)),      # one page, a few, many, two
