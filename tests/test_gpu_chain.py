@@ -143,9 +143,11 @@ def run_decode_steps(w, steps, permute, flags, group=1):
             check_selection(idx1, O.estimate(meta, q, table, cur, S), cur, S, w.k_pages)
         if flags & 4:
             assert (idx1[:, :, 0] == 0).all(), step
-        if flags & 8:
-            for b in range(w.batch):
-                assert ((idx1[b] == (int(cur[b]) - 1) // S).sum(axis=-1) == 1).all(), step
+        if flags & 8:               # the newest page, once: the first page goes before it
+            for b in range(w.batch):    # when the list has room for one page only
+                newest = (int(cur[b]) - 1) // S
+                if keff1[b] >= (2 if flags & 4 and newest != 0 else 1):
+                    assert ((idx1[b] == newest).sum(axis=-1) == 1).all(), step
         want, want_lse = O.sparse_decode(k_pool, v_pool, q, table, cur, idx1, scale)
         assert np.abs(out1 - want).max() <= ATTN_TOL, step
         assert np.abs(lse1 - want_lse).max() <= ATTN_TOL, step
@@ -167,6 +169,25 @@ def test_decode_step_ragged_batch(flags):
     w = synth.Workload(92, "ragged-step", 5, 3, (1, 16 * 3 + 7, 16 * 203 + 5, 16 * 64, 16 * 130 + 15),
                        token_budget=16 * 24, planted_per_head=4, decode_steps=24)
     run_decode_steps(w, steps=20, permute=True, flags=flags)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_decode_step_randomised_shapes(seed):
+    """Batch, KV heads, query heads per KV head, page size, sequence lengths, budget and
+    flags drawn at random (seeded), a few steps each through quest_decode_step."""
+    rng = np.random.default_rng(7000 + seed)
+    S = int(rng.choice([8, 16, 32, 64]))
+    batch, kv_heads = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+    group = int(rng.choice([1, 1, 2, 4]))
+    lens = [int(rng.choice([rng.integers(1, 2 * S), rng.integers(2 * S, 40 * S), rng.integers(40 * S, 260 * S)]))
+            for _ in range(batch)]
+    budget = S * int(rng.choice([1, 2, rng.integers(3, 40), rng.integers(40, 300)]))
+    flags = int(rng.choice([0, 1, 2, 3])) | int(rng.choice([0, 0, 4, 8, 12]))
+    w = synth.Workload(600 + seed, f"random-{seed}", batch, kv_heads, tuple(lens), token_budget=budget,
+                       planted_per_head=4, page_size=S, decode_steps=8)
+    print(f"seed {seed}: S={S} batch={batch} kv_heads={kv_heads} group={group} lens={lens} "
+          f"budget={budget} flags={flags}", flush=True)
+    run_decode_steps(w, steps=5, permute=True, flags=flags, group=group)
 
 
 @pytest.mark.parametrize("flags", [4 | 8, 1 | 4 | 8, 8])
