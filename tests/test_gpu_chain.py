@@ -171,7 +171,7 @@ def test_decode_step_ragged_batch(flags):
     run_decode_steps(w, steps=20, permute=True, flags=flags)
 
 
-@pytest.mark.parametrize("seed", range(8))
+@pytest.mark.parametrize("seed", range(24))
 def test_decode_step_randomised_shapes(seed):
     """Batch, KV heads, query heads per KV head, page size, sequence lengths, budget and
     flags drawn at random (seeded), a few steps each through quest_decode_step."""

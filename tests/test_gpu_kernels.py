@@ -296,7 +296,7 @@ def _random_scores(rng, shape, kind):
     raise AssertionError(kind)
 
 
-@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("seed", range(16))
 def test_topk_randomised_shapes(seed):
     """Row lengths, sequence lengths, budgets, policy flags and score distributions drawn
     at random (seeded): every list equals the oracle's, with and without a workspace."""
